@@ -1,0 +1,150 @@
+"""Pins for the oracle's integer rules: rank quantization (Section 2.1), the rank formulas
+(eq. 6 / eq. 7) and the sequential-freezing schedule (Algorithm 2)."""
+import math
+
+import oracle
+from conftest import read_golden
+
+
+# ---------------------------------------------------------------- printed examples (golden)
+def test_paper_examples():
+    for row in read_golden("paper_rank_examples.txt"):
+        kind = row[0]
+        if kind == "tucker_rank":
+            C, S, k = int(row[1]), int(row[2]), int(row[3])
+            alpha, beta = float(row[4]), float(row[5])
+            assert oracle.tucker_rank(C, S, k, alpha, beta) == (int(row[6]), int(row[7]))
+        elif kind == "quantize":
+            r, q = int(row[1]), int(row[2])
+            # every power-of-two granularity from 4 to 256 sends 257 to 256, in NEAREST and DOWN mode
+            for m in (4, 8, 16, 32, 64, 128, 256):
+                assert oracle.quantize_rank(r, m, oracle.ROUND_NEAREST) == q
+                assert oracle.quantize_rank(r, m, oracle.ROUND_DOWN) == q
+        elif kind == "compression_change_below":
+            ra, rb, C, S, k = (int(x) for x in row[1:6])
+            bound = float(row[6])
+
+            def ratio(r):
+                return C * S * k * k / (C * r + k * k * r * r + r * S)
+
+            assert abs(ratio(rb) / ratio(ra) - 1.0) < bound
+        elif kind == "rmin_range":
+            C, S, k = int(row[1]), int(row[2]), int(row[3])
+            r1, _ = oracle.tucker_rank(C, S, k, float(row[4]), float(row[5]))
+            assert int(row[6]) <= r1 <= int(row[7])
+        else:
+            raise AssertionError(kind)
+
+
+def test_alg2_truth_table():
+    for kind, parity, f0, f1, f2 in read_golden("alg2_truth_table.txt"):
+        k = oracle.KIND_SVD if kind == "svd" else oracle.KIND_TUCKER
+        want = int(f0) * 1 + int(f1) * 2 + (0 if f2 == "-" else int(f2) * 4)
+        for e in (int(parity), int(parity) + 2, int(parity) + 100, int(parity) + 2**40):
+            assert oracle.freeze_mask(k, e) == want
+
+
+def test_freeze_mask_complements_and_period():
+    for kind, bits in ((oracle.KIND_SVD, 0b11), (oracle.KIND_TUCKER, 0b111)):
+        for e in range(20):
+            a, b = oracle.freeze_mask(kind, e), oracle.freeze_mask(kind, e + 1)
+            assert a ^ b == bits          # what was frozen is released, the rest is frozen
+            assert a & b == 0
+            assert oracle.freeze_mask(kind, e + 2) == a
+
+
+# ---------------------------------------------------------------- eq. 6 / eq. 7
+def _tucker_params(C, S, k, r1, r2):
+    return C * r1 + k * k * r1 * r2 + r2 * S
+
+
+def test_tucker_rank_is_parameter_count_root():
+    """eq. 6 is the positive root of  C r1 + k^2 r1 r2 + r2 S = C S k^2 / alpha  with r2 = beta r1:
+    the returned r1 meets the budget and r1 + 1 does not (beta = 1)."""
+    for (C, S, k) in ((512, 512, 3), (64, 64, 3), (256, 512, 3), (128, 96, 5), (320, 64, 1), (48, 48, 7)):
+        for alpha in (1.5, 2.0, 3.0, 4.0, 8.0):
+            r1, r2 = oracle.tucker_rank(C, S, k, alpha, 1.0)
+            assert r1 == r2 or r2 == min(r1, S) or r1 == min(r2, C)
+            budget = C * S * k * k / alpha
+            if 1 < r1 < min(C, S):
+                assert _tucker_params(C, S, k, r1, r1) <= budget < _tucker_params(C, S, k, r1 + 1, r1 + 1)
+
+
+def test_tucker_rank_worked_numbers():
+    # closed form of the paper's example evaluates to 309.59... (alpha=2) and 244.1... (alpha+1=3)
+    b = (512 + 512) / 9.0
+    x2 = (-b + math.sqrt(b * b + 4 * 512 * 512 / 2.0)) / 2
+    x3 = (-b + math.sqrt(b * b + 4 * 512 * 512 / 3.0)) / 2
+    assert 309 < x2 < 310 and 244 < x3 < 245
+    assert oracle.tucker_rank(512, 512, 3, 2.0)[0] == 309
+    assert oracle.tucker_rank(512, 512, 3, 3.0)[0] == 244
+    # the 2x example really is 2x: parameter ratio at 309 is 2.0066
+    assert abs(512 * 512 * 9 / _tucker_params(512, 512, 3, 309, 309) - 2.0066) < 1e-4
+
+
+def test_tucker_rank_beta():
+    r1, r2 = oracle.tucker_rank(256, 512, 3, 2.0, 2.0)
+    assert r2 == 2 * r1
+    budget = 256 * 512 * 9 / 2.0
+    assert _tucker_params(256, 512, 3, r1, 2 * r1) <= budget < _tucker_params(256, 512, 3, r1 + 1, 2 * (r1 + 1))
+
+
+def test_svd_rank():
+    for (n_in, n_out) in ((768, 768), (768, 3072), (4096, 4096), (1000, 10)):
+        for alpha in (1.0, 2.0, 3.5):
+            r = oracle.svd_rank(n_in, n_out, alpha)
+            if 1 < r < min(n_in, n_out):
+                assert r * (n_in + n_out) <= n_in * n_out / alpha < (r + 1) * (n_in + n_out)
+    assert oracle.svd_rank(768, 768, 1.0) == 384
+    assert oracle.svd_rank(4, 4, 1e-9) == 4          # clamped to min(in,out)
+    assert oracle.svd_rank(4, 4, 1e9) == 1
+
+
+# ---------------------------------------------------------------- quantization: brute force + properties
+def _nearest_multiple_ties_up(r, m):
+    """One-line definition: the multiple of m closest to r, the larger one on a tie."""
+    cands = [(abs(q - r), -q, q) for q in range(0, r + 2 * m, m)]
+    return min(cands)[2]
+
+
+def test_quantize_brute_force():
+    for m in (1, 3, 8, 16, 32, 64, 128):
+        prev = {0: 0, 1: 0, 2: 0}
+        for r in range(1, 2049):
+            qn = oracle.quantize_rank(r, m, oracle.ROUND_NEAREST)
+            qd = oracle.quantize_rank(r, m, oracle.ROUND_DOWN)
+            qu = oracle.quantize_rank(r, m, oracle.ROUND_UP)
+            want_n = max(_nearest_multiple_ties_up(r, m), m)   # confined to >= 1
+            assert qn == want_n, (r, m, qn, want_n)
+            assert qd == max((r // m) * m, m)
+            assert qu == -(-r // m) * m
+            for mode, q in ((0, qn), (1, qd), (2, qu)):
+                assert q % m == 0
+                assert oracle.quantize_rank(q, m, mode) == q      # idempotent
+                assert q >= prev[mode]                             # monotone in r
+                prev[mode] = q
+            if r >= m:
+                assert 2 * abs(qn - r) <= m and 0 <= r - qd < m and 0 <= qu - r < m
+            if m == 1:
+                assert qn == qd == qu == r
+
+
+def test_quantize_examples_and_bounds():
+    assert oracle.quantize_rank(200, 16) == 208        # exact tie between 192 and 208 goes up
+    assert oracle.quantize_rank(200, 16, oracle.ROUND_DOWN) == 192
+    assert oracle.quantize_rank(309, 16, oracle.ROUND_DOWN) == 304
+    assert oracle.quantize_rank(309, 16, oracle.ROUND_UP) == 320
+    assert oracle.quantize_rank(309, 64) == 320
+    # bounds: stay inside [r_min, r_max] on multiples of m
+    assert oracle.quantize_rank(250, 64, oracle.ROUND_NEAREST, 1, 200) == 192
+    assert oracle.quantize_rank(250, 64, oracle.ROUND_DOWN, 257, 400) == 320
+    assert oracle.quantize_rank(10, 64, oracle.ROUND_DOWN, 1, 1000) == 64
+    # no multiple inside the bounds: the rank is returned as it came
+    assert oracle.quantize_rank(250, 64, oracle.ROUND_NEAREST, 200, 250) == 250
+    assert oracle.quantize_rank(5, 16, oracle.ROUND_NEAREST, 1, 10) == 5
+    # paper's direction (Algorithm 1 only lowers the rank) with eq. 7 as the floor
+    rmin = oracle.tucker_rank(512, 512, 3, 3.0)[0]
+    assert oracle.quantize_rank(309, 64, oracle.ROUND_DOWN, rmin, 512) == 256
+    # bad arguments
+    for args in ((0, 16, 0, 1, 100), (10, 0, 0, 1, 100), (10, 16, 3, 1, 100), (10, 16, 0, 5, 4)):
+        assert oracle.quantize_rank(*args) < 0
