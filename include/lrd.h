@@ -1,0 +1,216 @@
+/*
+ * lrd.h -- C ABI of the MI355X (gfx950) library for low-rank-decomposed layers.
+ *
+ * Method: Hajimolahoseini, Ahmed, Liu, "Training Acceleration of Low-Rank Decomposed Networks
+ * using Sequential Freezing and Rank Quantization".  The library evaluates the forward and
+ * backward pass of
+ *   - an SVD-decomposed fully connected / 1x1 layer: one layer becomes two consecutive layers
+ *     through a rank-r bottleneck (Section 2, eq. 1-2, Fig. 1), and
+ *   - a Tucker-2-decomposed k x k convolution: 1x1 -> k x k core -> 1x1 (Section 2, eq. 4),
+ * with the paper's two accelerations built in: rank quantization (Section 2.1) and sequential
+ * freezing (Section 2.2, Algorithm 2), where a frozen factor's weight-gradient product is skipped.
+ *
+ * Orientation.  The paper writes W in R^{C x S} (C inputs, S outputs) and W' = U' Sigma' V'^T
+ * (eq. 2), so its U' is the input-side factor.  This ABI uses the framework orientation
+ * W[out x in] = (paper W)^T ~= U.V:
+ *     V [r x in]   applied first  = the paper's decomposed layer L_r(0)
+ *     U [out x r]  applied second = the paper's decomposed layer L_r(1)
+ *     H = X.V^T [T x r],  Y = H.U^T [T x out].
+ * Tucker-2: P1 [r1 x C] = L_r(0), G [r2 x k x k x r1] = L_r(1) (core), P2 [S x r2] = L_r(2).
+ * The one-time factorization that produces the factors (eq. 1, 2, 4) is a host step outside
+ * this ABI.
+ *
+ * Conventions common to every device entry point
+ *   - All matrix arguments are DEVICE pointers to dense row-major arrays whose leading dimension
+ *     equals their logical width; convolution activations are NHWC, conv weights [O][k][k][I].
+ *   - dtype LRD_BF16: activations and factors are bfloat16, products accumulate in fp32,
+ *     activation outputs (Y, dX, H_save, ...) are bfloat16, weight gradients are fp32.
+ *     dtype LRD_F32: everything is fp32.
+ *   - The caller owns every buffer, including the workspace `ws` (size from the matching
+ *     *_workspace_bytes query; may be NULL when that query returns 0).  The library keeps no
+ *     device memory and no mutable global state.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default stream).
+ *     No call synchronises or allocates.
+ *   - Arguments are validated on the host before anything is launched; on a non-OK status
+ *     nothing has been written.  LRD_ERR_INVALID_ARG: non-positive sizes, rank larger than the
+ *     layer allows, NULL for a required pointer, unknown dtype or mask bits.  LRD_ERR_ALIGNMENT:
+ *     a base pointer that is not 16-byte aligned.  LRD_ERR_WORKSPACE: ws_bytes too small.
+ *     LRD_ERR_RUNTIME: the HIP runtime refused a launch.
+ *   - Any rank 1 <= r <= min(in,out) is legal.  Ranks that are multiples of 8/16/32 select
+ *     faster code (vector loads, whole MFMA tiles); results never depend on the code path
+ *     beyond fp32 summation order.
+ *   - Freeze mask: bit i set <=> L_r(i) is frozen.  A frozen factor's gradient buffer is neither
+ *     read nor written (it may be NULL); the gradient with respect to the layer input still
+ *     flows through the frozen factor.  Gradients of trainable factors are overwritten.
+ */
+#ifndef LRD_H
+#define LRD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LRD_OK = 0,
+    LRD_ERR_INVALID_ARG = 1,
+    LRD_ERR_UNSUPPORTED = 2,
+    LRD_ERR_ALIGNMENT = 3,
+    LRD_ERR_WORKSPACE = 4,
+    LRD_ERR_RUNTIME = 5
+} lrd_status;
+
+typedef enum { LRD_F32 = 0, LRD_BF16 = 1 } lrd_dtype;
+
+enum { LRD_KIND_SVD = 0, LRD_KIND_TUCKER = 1 };
+enum { LRD_FREEZE_L0 = 1u, LRD_FREEZE_L1 = 2u, LRD_FREEZE_L2 = 4u };
+enum { LRD_ROUND_NEAREST = 0, LRD_ROUND_DOWN = 1, LRD_ROUND_UP = 2 };
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char* lrd_status_string(lrd_status s);
+
+/* ------------------------------------------------------------------------------------------
+ * Host-only integer rules (pure functions, no device involved)
+ * ---------------------------------------------------------------------------------------- */
+
+/*
+ * Rank quantization, Section 2.1: a rank computed from a compression ratio (e.g. 257 or 309) is
+ * moved to a nearby multiple of `multiple` on which the matrix units run whole tiles (the
+ * paper's example: 257 -> 256).  mode LRD_ROUND_NEAREST picks the closest multiple, the larger
+ * one on a tie; LRD_ROUND_DOWN the next multiple <= r (the direction Algorithm 1 searches in);
+ * LRD_ROUND_UP the next multiple >= r.  The result is confined to the multiples that lie in
+ * [max(r_min,1), r_max]; if there is none, r is returned unchanged.
+ * Returns the quantized rank, or -LRD_ERR_INVALID_ARG if r < 1, multiple < 1, r_min > r_max or
+ * mode is unknown.
+ */
+int32_t lrd_quantize_rank(int32_t r, int32_t multiple, int32_t mode, int32_t r_min, int32_t r_max);
+
+/*
+ * Sequential freezing, Algorithm 2: the freeze mask of a decomposed layer at epoch `epoch`
+ * (0-based).  Even epoch: L_r(0) (and L_r(2) for Tucker) frozen, L_r(1) trains; odd epoch: the
+ * complement.  kind is LRD_KIND_SVD or LRD_KIND_TUCKER (any other value is read as SVD).
+ * Regular (non-sequential) freezing is the mask of epoch 0 kept for the whole run.
+ */
+uint32_t lrd_freeze_mask(int32_t kind, int64_t epoch);
+
+/*
+ * Tucker-2 ranks for compression ratio alpha, eq. 6 (r2 = beta * r1); called with alpha + 1 it
+ * is the lower bound R_min of eq. 7.  Both ranks are rounded down (the paper's worked example,
+ * [512,512,3,3] at 2x -> 309) and confined to [1,C] and [1,S].
+ */
+lrd_status lrd_tucker_rank(int64_t C, int64_t S, int32_t k, double alpha, double beta,
+                           int32_t* r1, int32_t* r2);
+
+/*
+ * Rank of an SVD pair for compression ratio alpha: floor(in*out / (alpha*(in+out))), confined
+ * to [1, min(in,out)] (same parameter-count argument as eq. 6).  Negative on bad arguments.
+ */
+int32_t lrd_svd_rank(int64_t in, int64_t out, double alpha);
+
+/* ------------------------------------------------------------------------------------------
+ * SVD-decomposed linear layer (Section 2, Fig. 1; freezing: Section 2.2)
+ * ---------------------------------------------------------------------------------------- */
+
+/* Bytes of workspace lrd_linear_fwd / lrd_linear_bwd need for these sizes (upper bound over
+ * every nullable-argument combination).  0 on bad arguments. */
+size_t lrd_linear_workspace_bytes(int64_t T, int64_t in, int64_t out, int64_t r, lrd_dtype dt,
+                                  uint32_t freeze_mask);
+
+/*
+ * Forward: H = X.V^T, Y = H.U^T (+ bias).
+ *   X [T x in], V [r x in], U [out x r], bias [out] fp32 or NULL, Y [T x out] (written),
+ *   H_save [T x r] in the activation dtype or NULL: when given it receives H for the backward
+ *   pass (needed there only if U is trainable).
+ */
+lrd_status lrd_linear_fwd(const void* X, const void* V, const void* U, const float* bias, void* Y,
+                          void* H_save, int64_t T, int64_t in, int64_t out, int64_t r,
+                          lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Backward: dH = dY.U, dX = dH.V, dU = dY^T.H unless bit1 of freeze_mask, dV = dH^T.X unless
+ * bit0.
+ *   dY [T x out]; X [T x in] (required if V is trainable or H is NULL); H [T x r] as saved by
+ *   the forward (NULL: recomputed from X into the workspace when U is trainable);
+ *   dX [T x in] or NULL (a first layer needs none); dV [r x in] fp32, dU [out x r] fp32,
+ *   dbias [out] fp32 or NULL.
+ */
+lrd_status lrd_linear_bwd(const void* dY, const void* X, const void* H, const void* V,
+                          const void* U, void* dX, float* dV, float* dU, float* dbias,
+                          uint32_t freeze_mask, int64_t T, int64_t in, int64_t out, int64_t r,
+                          lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * The undecomposed layer Y = X.W^T (+ bias), dX = dY.W, dW = dY^T.X: the "original layer" whose
+ * time Algorithm 1 compares a decomposed layer against.  W [out x in]; dX, dW nullable.
+ */
+size_t lrd_dense_linear_workspace_bytes(int64_t T, int64_t in, int64_t out, lrd_dtype dt);
+lrd_status lrd_dense_linear_fwd(const void* X, const void* W, const float* bias, void* Y,
+                                int64_t T, int64_t in, int64_t out, lrd_dtype dt, void* ws,
+                                size_t ws_bytes, void* hip_stream);
+lrd_status lrd_dense_linear_bwd(const void* dY, const void* X, const void* W, void* dX, float* dW,
+                                int64_t T, int64_t in, int64_t out, lrd_dtype dt, void* ws,
+                                size_t ws_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Tucker-2-decomposed convolution (Section 2, eq. 4: 1x1 -> k x k core -> 1x1)
+ * ---------------------------------------------------------------------------------------- */
+
+/* Geometry of one decomposed convolution.  Stride and padding act on the k x k core; the two
+ * 1x1 layers have stride 1 and no padding.  Ho = (H + 2*pad - k)/stride + 1, same for Wo. */
+typedef struct {
+    int64_t N, H, W;   /* batch, input height, input width */
+    int64_t C, S;      /* input channels, output channels   */
+    int64_t r1, r2;    /* Tucker ranks: C -> r1 -> r2 -> S  */
+    int32_t k, stride, pad;
+} lrd_conv_geom;
+
+size_t lrd_tucker_conv_workspace_bytes(const lrd_conv_geom* g, lrd_dtype dt, uint32_t freeze_mask);
+
+/*
+ * Forward: A = X.P1^T (per pixel), B = conv_kxk(A, G), Y = B.P2^T (per pixel).
+ *   X [N,H,W,C], P1 [r1 x C], G [r2,k,k,r1], P2 [S x r2], Y [N,Ho,Wo,S] (written);
+ *   A_save [N,H,W,r1] and B_save [N,Ho,Wo,r2] or NULL: the intermediates, kept for the backward.
+ */
+lrd_status lrd_tucker_conv_fwd(const void* X, const void* P1, const void* G, const void* P2,
+                               void* Y, void* A_save, void* B_save, const lrd_conv_geom* g,
+                               lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Backward: dB = dY.P2, dA = conv^T(dB, G), dX = dA.P1; dP1 = dA^T.X unless bit0,
+ * dG[o,u,v,i] = sum_pixels dB[..,o] A[shifted ..,i] unless bit1, dP2 = dY^T.B unless bit2.
+ *   A, B as saved by the forward (NULL: recomputed into the workspace when needed);
+ *   dX nullable; dP1 [r1 x C], dG [r2,k,k,r1], dP2 [S x r2] fp32.
+ */
+lrd_status lrd_tucker_conv_bwd(const void* dY, const void* X, const void* A, const void* B,
+                               const void* P1, const void* G, const void* P2, void* dX,
+                               float* dP1, float* dG, float* dP2, uint32_t freeze_mask,
+                               const lrd_conv_geom* g, lrd_dtype dt, void* ws, size_t ws_bytes,
+                               void* hip_stream);
+
+/*
+ * The undecomposed k x k convolution (geometry fields r1, r2 ignored): Y = conv(X, W),
+ * dX = conv^T(dY, W), dW = wgrad(dY, X); W [S,k,k,C].  dX, dW nullable.
+ */
+size_t lrd_dense_conv_workspace_bytes(const lrd_conv_geom* g, lrd_dtype dt);
+lrd_status lrd_dense_conv_fwd(const void* X, const void* W, void* Y, const lrd_conv_geom* g,
+                              lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream);
+lrd_status lrd_dense_conv_bwd(const void* dY, const void* X, const void* W, void* dX, float* dW,
+                              const lrd_conv_geom* g, lrd_dtype dt, void* ws, size_t ws_bytes,
+                              void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Glue between stacked layers (not part of the method; used by the layer-stack workloads)
+ * ---------------------------------------------------------------------------------------- */
+
+/* GELU in its erf form, A = Z * Phi(Z), and its backward dZ = dA * (Phi(Z) + Z * phi(Z));
+ * n elements of the activation dtype. */
+lrd_status lrd_gelu_fwd(const void* Z, void* A, int64_t n, lrd_dtype dt, void* hip_stream);
+lrd_status lrd_gelu_bwd(const void* dA, const void* Z, void* dZ, int64_t n, lrd_dtype dt,
+                        void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LRD_H */

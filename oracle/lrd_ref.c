@@ -161,36 +161,40 @@ void lrd_ref_linear_bwd(const double* dY, const double* X, const double* H, cons
 {
 #pragma omp parallel for schedule(static)
     for (int64_t t = 0; t < T; ++t) {
-        for (int64_t j = 0; j < r; ++j) {
-            double s = 0.0;
-            for (int64_t o = 0; o < out; ++o) s += dY[t * out + o] * U[o * r + j];
-            dH[t * r + j] = s;
+        /* every sum runs over its index in ascending order; the innermost loop walks the
+         * contiguous index of the output row so that memory is read in order */
+        for (int64_t j = 0; j < r; ++j) dH[t * r + j] = 0.0;
+        for (int64_t o = 0; o < out; ++o) {
+            double g = dY[t * out + o];
+            for (int64_t j = 0; j < r; ++j) dH[t * r + j] += g * U[o * r + j];
         }
         if (dX) {
-            for (int64_t i = 0; i < in; ++i) {
-                double s = 0.0;
-                for (int64_t j = 0; j < r; ++j) s += dH[t * r + j] * V[j * in + i];
-                dX[t * in + i] = s;
+            for (int64_t i = 0; i < in; ++i) dX[t * in + i] = 0.0;
+            for (int64_t j = 0; j < r; ++j) {
+                double g = dH[t * r + j];
+                for (int64_t i = 0; i < in; ++i) dX[t * in + i] += g * V[j * in + i];
             }
         }
     }
     if (!(mask & LRD_REF_FREEZE_L1) && dU) {
 #pragma omp parallel for schedule(static)
-        for (int64_t o = 0; o < out; ++o)
-            for (int64_t j = 0; j < r; ++j) {
-                double s = 0.0;
-                for (int64_t t = 0; t < T; ++t) s += dY[t * out + o] * H[t * r + j];
-                dU[o * r + j] = s;
+        for (int64_t o = 0; o < out; ++o) {
+            for (int64_t j = 0; j < r; ++j) dU[o * r + j] = 0.0;
+            for (int64_t t = 0; t < T; ++t) {
+                double g = dY[t * out + o];
+                for (int64_t j = 0; j < r; ++j) dU[o * r + j] += g * H[t * r + j];
             }
+        }
     }
     if (!(mask & LRD_REF_FREEZE_L0) && dV) {
 #pragma omp parallel for schedule(static)
-        for (int64_t j = 0; j < r; ++j)
-            for (int64_t i = 0; i < in; ++i) {
-                double s = 0.0;
-                for (int64_t t = 0; t < T; ++t) s += dH[t * r + j] * X[t * in + i];
-                dV[j * in + i] = s;
+        for (int64_t j = 0; j < r; ++j) {
+            for (int64_t i = 0; i < in; ++i) dV[j * in + i] = 0.0;
+            for (int64_t t = 0; t < T; ++t) {
+                double g = dH[t * r + j];
+                for (int64_t i = 0; i < in; ++i) dV[j * in + i] += g * X[t * in + i];
             }
+        }
     }
     if (dbias) {
         for (int64_t o = 0; o < out; ++o) {
@@ -219,21 +223,23 @@ void lrd_ref_dense_linear_bwd(const double* dY, const double* X, const double* W
 {
     if (dX) {
 #pragma omp parallel for schedule(static)
-        for (int64_t t = 0; t < T; ++t)
-            for (int64_t i = 0; i < in; ++i) {
-                double s = 0.0;
-                for (int64_t o = 0; o < out; ++o) s += dY[t * out + o] * W[o * in + i];
-                dX[t * in + i] = s;
+        for (int64_t t = 0; t < T; ++t) {
+            for (int64_t i = 0; i < in; ++i) dX[t * in + i] = 0.0;
+            for (int64_t o = 0; o < out; ++o) {
+                double g = dY[t * out + o];
+                for (int64_t i = 0; i < in; ++i) dX[t * in + i] += g * W[o * in + i];
             }
+        }
     }
     if (dW) {
 #pragma omp parallel for schedule(static)
-        for (int64_t o = 0; o < out; ++o)
-            for (int64_t i = 0; i < in; ++i) {
-                double s = 0.0;
-                for (int64_t t = 0; t < T; ++t) s += dY[t * out + o] * X[t * in + i];
-                dW[o * in + i] = s;
+        for (int64_t o = 0; o < out; ++o) {
+            for (int64_t i = 0; i < in; ++i) dW[o * in + i] = 0.0;
+            for (int64_t t = 0; t < T; ++t) {
+                double g = dY[t * out + o];
+                for (int64_t i = 0; i < in; ++i) dW[o * in + i] += g * X[t * in + i];
             }
+        }
     }
 }
 
@@ -297,26 +303,27 @@ void lrd_ref_conv_dgrad(const double* dY, const double* W, double* dX, int64_t N
 #pragma omp parallel for schedule(static) collapse(2)
     for (int64_t n = 0; n < N; ++n)
         for (int64_t a = 0; a < Hh; ++a)
-            for (int64_t b = 0; b < Ww; ++b)
-                for (int64_t i = 0; i < I; ++i) {
-                    double acc = 0.0;
-                    for (int32_t u = 0; u < k; ++u) {
-                        int64_t ys = a + p - u;
-                        if (ys < 0 || ys % s != 0) continue;
-                        int64_t y = ys / s;
-                        if (y >= Ho) continue;
-                        for (int32_t v = 0; v < k; ++v) {
-                            int64_t xs = b + p - v;
-                            if (xs < 0 || xs % s != 0) continue;
-                            int64_t x = xs / s;
-                            if (x >= Wo) continue;
-                            const double* gp = dY + ((n * Ho + y) * Wo + x) * O;
-                            for (int64_t o = 0; o < O; ++o)
-                                acc += gp[o] * W[((o * k + u) * k + v) * I + i];
+            for (int64_t b = 0; b < Ww; ++b) {
+                double* dx = dX + ((n * Hh + a) * Ww + b) * I;
+                for (int64_t i = 0; i < I; ++i) dx[i] = 0.0;
+                for (int32_t u = 0; u < k; ++u) {
+                    int64_t ys = a + p - u;
+                    if (ys < 0 || ys % s != 0) continue;
+                    int64_t y = ys / s;
+                    if (y >= Ho) continue;
+                    for (int32_t v = 0; v < k; ++v) {
+                        int64_t xs = b + p - v;
+                        if (xs < 0 || xs % s != 0) continue;
+                        int64_t x = xs / s;
+                        if (x >= Wo) continue;
+                        const double* gp = dY + ((n * Ho + y) * Wo + x) * O;
+                        for (int64_t o = 0; o < O; ++o) {
+                            const double* wp = W + ((o * k + u) * k + v) * I;
+                            for (int64_t i = 0; i < I; ++i) dx[i] += gp[o] * wp[i];
                         }
                     }
-                    dX[((n * Hh + a) * Ww + b) * I + i] = acc;
                 }
+            }
 }
 
 /* dW[o,u,v,i] = sum_{n,y,x} dY[n,y,x,o] X[n, y*s+u-p, x*s+v-p, i] */
@@ -325,24 +332,26 @@ void lrd_ref_conv_wgrad(const double* dY, const double* X, double* dW, int64_t N
 {
     int64_t Ho = conv_out_dim(Hh, k, s, p), Wo = conv_out_dim(Ww, k, s, p);
 #pragma omp parallel for schedule(static)
-    for (int64_t o = 0; o < O; ++o)
-        for (int32_t u = 0; u < k; ++u)
-            for (int32_t v = 0; v < k; ++v)
-                for (int64_t i = 0; i < I; ++i) {
-                    double acc = 0.0;
-                    for (int64_t n = 0; n < N; ++n)
-                        for (int64_t y = 0; y < Ho; ++y) {
-                            int64_t yy = y * s + u - p;
-                            if (yy < 0 || yy >= Hh) continue;
-                            for (int64_t x = 0; x < Wo; ++x) {
-                                int64_t xx = x * s + v - p;
-                                if (xx < 0 || xx >= Ww) continue;
-                                acc += dY[((n * Ho + y) * Wo + x) * O + o] *
-                                       X[((n * Hh + yy) * Ww + xx) * I + i];
-                            }
+    for (int64_t o = 0; o < O; ++o) {
+        for (int64_t e = 0; e < (int64_t)k * k * I; ++e) dW[o * k * k * I + e] = 0.0;
+        /* pixels in ascending (n,y,x) order for every weight entry */
+        for (int64_t n = 0; n < N; ++n)
+            for (int64_t y = 0; y < Ho; ++y)
+                for (int64_t x = 0; x < Wo; ++x) {
+                    double g = dY[((n * Ho + y) * Wo + x) * O + o];
+                    for (int32_t u = 0; u < k; ++u) {
+                        int64_t yy = y * s + u - p;
+                        if (yy < 0 || yy >= Hh) continue;
+                        for (int32_t v = 0; v < k; ++v) {
+                            int64_t xx = x * s + v - p;
+                            if (xx < 0 || xx >= Ww) continue;
+                            const double* xp = X + ((n * Hh + yy) * Ww + xx) * I;
+                            double* wp = dW + ((o * k + u) * k + v) * I;
+                            for (int64_t i = 0; i < I; ++i) wp[i] += g * xp[i];
                         }
-                    dW[((o * k + u) * k + v) * I + i] = acc;
+                    }
                 }
+    }
 }
 
 /* A pointwise (1x1) layer over P pixels: Out[p,o] = sum_i In[p,i] M[o,i]. */
@@ -363,12 +372,13 @@ static void pointwise_dgrad(const double* dOut, const double* M, double* dIn, in
                             int64_t O)
 {
 #pragma omp parallel for schedule(static)
-    for (int64_t q = 0; q < P; ++q)
-        for (int64_t i = 0; i < I; ++i) {
-            double s = 0.0;
-            for (int64_t o = 0; o < O; ++o) s += dOut[q * O + o] * M[o * I + i];
-            dIn[q * I + i] = s;
+    for (int64_t q = 0; q < P; ++q) {
+        for (int64_t i = 0; i < I; ++i) dIn[q * I + i] = 0.0;
+        for (int64_t o = 0; o < O; ++o) {
+            double g = dOut[q * O + o];
+            for (int64_t i = 0; i < I; ++i) dIn[q * I + i] += g * M[o * I + i];
         }
+    }
 }
 
 /* dM[o,i] = sum_p dOut[p,o] In[p,i] */
@@ -376,12 +386,13 @@ static void pointwise_wgrad(const double* dOut, const double* In, double* dM, in
                             int64_t O)
 {
 #pragma omp parallel for schedule(static)
-    for (int64_t o = 0; o < O; ++o)
-        for (int64_t i = 0; i < I; ++i) {
-            double s = 0.0;
-            for (int64_t q = 0; q < P; ++q) s += dOut[q * O + o] * In[q * I + i];
-            dM[o * I + i] = s;
+    for (int64_t o = 0; o < O; ++o) {
+        for (int64_t i = 0; i < I; ++i) dM[o * I + i] = 0.0;
+        for (int64_t q = 0; q < P; ++q) {
+            double g = dOut[q * O + o];
+            for (int64_t i = 0; i < I; ++i) dM[o * I + i] += g * In[q * I + i];
         }
+    }
 }
 
 /*

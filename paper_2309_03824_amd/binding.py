@@ -1,0 +1,254 @@
+"""ctypes binding of liblrd.so: the same entry points as include/lrd.h, taking torch tensors.
+
+Argument marshalling only.  torch supplies device memory and the stream; every arithmetic step
+runs in the library's HIP kernels.  There is no CPU fallback: if the library cannot be loaded the
+import fails, and a non-OK status raises LrdError.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, Structure, c_char_p, c_double, c_int32, c_int64, c_size_t, c_uint32, c_void_p
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblrd.so")
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_ALIGNMENT, ERR_WORKSPACE, ERR_RUNTIME = range(6)
+F32, BF16 = 0, 1
+KIND_SVD, KIND_TUCKER = 0, 1
+FREEZE_L0, FREEZE_L1, FREEZE_L2 = 1, 2, 4
+ROUND_NEAREST, ROUND_DOWN, ROUND_UP = 0, 1, 2
+
+EXPORTS = (
+    "lrd_status_string", "lrd_quantize_rank", "lrd_freeze_mask", "lrd_tucker_rank", "lrd_svd_rank",
+    "lrd_linear_workspace_bytes", "lrd_linear_fwd", "lrd_linear_bwd",
+    "lrd_dense_linear_workspace_bytes", "lrd_dense_linear_fwd", "lrd_dense_linear_bwd",
+    "lrd_tucker_conv_workspace_bytes", "lrd_tucker_conv_fwd", "lrd_tucker_conv_bwd",
+    "lrd_dense_conv_workspace_bytes", "lrd_dense_conv_fwd", "lrd_dense_conv_bwd",
+    "lrd_gelu_fwd", "lrd_gelu_bwd",
+)
+
+
+class LrdError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        super().__init__(f"{where}: {status_string(status)}")
+
+
+class ConvGeom(Structure):
+    _fields_ = [("N", c_int64), ("H", c_int64), ("W", c_int64), ("C", c_int64), ("S", c_int64),
+                ("r1", c_int64), ("r2", c_int64), ("k", c_int32), ("stride", c_int32), ("pad", c_int32)]
+
+    def out_hw(self):
+        return ((self.H + 2 * self.pad - self.k) // self.stride + 1,
+                (self.W + 2 * self.pad - self.k) // self.stride + 1)
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(LIB_PATH)
+    P, I64, SZ, U32 = c_void_p, c_int64, c_size_t, c_uint32
+    G = POINTER(ConvGeom)
+    lib.lrd_status_string.restype = c_char_p
+    lib.lrd_status_string.argtypes = [ctypes.c_int]
+    lib.lrd_quantize_rank.restype = c_int32
+    lib.lrd_quantize_rank.argtypes = [c_int32] * 5
+    lib.lrd_freeze_mask.restype = c_uint32
+    lib.lrd_freeze_mask.argtypes = [c_int32, c_int64]
+    lib.lrd_tucker_rank.restype = ctypes.c_int
+    lib.lrd_tucker_rank.argtypes = [I64, I64, c_int32, c_double, c_double, POINTER(c_int32), POINTER(c_int32)]
+    lib.lrd_svd_rank.restype = c_int32
+    lib.lrd_svd_rank.argtypes = [I64, I64, c_double]
+    lib.lrd_linear_workspace_bytes.restype = SZ
+    lib.lrd_linear_workspace_bytes.argtypes = [I64] * 4 + [ctypes.c_int, U32]
+    lib.lrd_linear_fwd.restype = ctypes.c_int
+    lib.lrd_linear_fwd.argtypes = [P] * 6 + [I64] * 4 + [ctypes.c_int, P, SZ, P]
+    lib.lrd_linear_bwd.restype = ctypes.c_int
+    lib.lrd_linear_bwd.argtypes = [P] * 9 + [U32] + [I64] * 4 + [ctypes.c_int, P, SZ, P]
+    lib.lrd_dense_linear_workspace_bytes.restype = SZ
+    lib.lrd_dense_linear_workspace_bytes.argtypes = [I64] * 3 + [ctypes.c_int]
+    lib.lrd_dense_linear_fwd.restype = ctypes.c_int
+    lib.lrd_dense_linear_fwd.argtypes = [P] * 4 + [I64] * 3 + [ctypes.c_int, P, SZ, P]
+    lib.lrd_dense_linear_bwd.restype = ctypes.c_int
+    lib.lrd_dense_linear_bwd.argtypes = [P] * 5 + [I64] * 3 + [ctypes.c_int, P, SZ, P]
+    lib.lrd_tucker_conv_workspace_bytes.restype = SZ
+    lib.lrd_tucker_conv_workspace_bytes.argtypes = [G, ctypes.c_int, U32]
+    lib.lrd_tucker_conv_fwd.restype = ctypes.c_int
+    lib.lrd_tucker_conv_fwd.argtypes = [P] * 7 + [G, ctypes.c_int, P, SZ, P]
+    lib.lrd_tucker_conv_bwd.restype = ctypes.c_int
+    lib.lrd_tucker_conv_bwd.argtypes = [P] * 11 + [U32, G, ctypes.c_int, P, SZ, P]
+    lib.lrd_dense_conv_workspace_bytes.restype = SZ
+    lib.lrd_dense_conv_workspace_bytes.argtypes = [G, ctypes.c_int]
+    lib.lrd_dense_conv_fwd.restype = ctypes.c_int
+    lib.lrd_dense_conv_fwd.argtypes = [P] * 3 + [G, ctypes.c_int, P, SZ, P]
+    lib.lrd_dense_conv_bwd.restype = ctypes.c_int
+    lib.lrd_dense_conv_bwd.argtypes = [P] * 5 + [G, ctypes.c_int, P, SZ, P]
+    lib.lrd_gelu_fwd.restype = ctypes.c_int
+    lib.lrd_gelu_fwd.argtypes = [P, P, I64, ctypes.c_int, P]
+    lib.lrd_gelu_bwd.restype = ctypes.c_int
+    lib.lrd_gelu_bwd.argtypes = [P, P, P, I64, ctypes.c_int, P]
+    return lib
+
+
+_lib = _load()
+
+
+# ------------------------------------------------------------------------------- marshalling
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("device tensor expected")
+    if not t.is_contiguous():
+        raise ValueError("contiguous tensor expected")
+    return t.data_ptr()
+
+
+def _dt(t) -> int:
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float32:
+        return F32
+    raise ValueError(f"unsupported dtype {t.dtype}")
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _ws(ws):
+    return (None, 0) if ws is None else (ws.data_ptr(), ws.numel() * ws.element_size())
+
+
+def _check(status, where):
+    if status != OK:
+        raise LrdError(status, where)
+
+
+def status_string(status: int) -> str:
+    return _lib.lrd_status_string(int(status)).decode()
+
+
+# ------------------------------------------------------------------------------- integer rules
+def quantize_rank(r: int, multiple: int, mode: int = ROUND_NEAREST, r_min: int = 1,
+                  r_max: int = 2**31 - 1) -> int:
+    q = _lib.lrd_quantize_rank(r, multiple, mode, r_min, r_max)
+    if q < 0:
+        raise LrdError(-q, "lrd_quantize_rank")
+    return int(q)
+
+
+def freeze_mask(kind: int, epoch: int) -> int:
+    return int(_lib.lrd_freeze_mask(kind, epoch))
+
+
+def tucker_rank(C: int, S: int, k: int, alpha: float, beta: float = 1.0):
+    r1, r2 = c_int32(0), c_int32(0)
+    _check(_lib.lrd_tucker_rank(C, S, k, alpha, beta, ctypes.byref(r1), ctypes.byref(r2)), "lrd_tucker_rank")
+    return int(r1.value), int(r2.value)
+
+
+def svd_rank(n_in: int, n_out: int, alpha: float) -> int:
+    r = _lib.lrd_svd_rank(n_in, n_out, alpha)
+    if r < 0:
+        raise LrdError(-r, "lrd_svd_rank")
+    return int(r)
+
+
+# ------------------------------------------------------------------------------- linear pair
+def linear_workspace_bytes(T, n_in, n_out, r, dtype, freeze_mask=0) -> int:
+    return int(_lib.lrd_linear_workspace_bytes(T, n_in, n_out, r, dtype, freeze_mask))
+
+
+def linear_fwd(X, V, U, bias, Y, H_save, ws=None, stream=None):
+    T, n_in = X.shape
+    r, n_out = V.shape[0], U.shape[0]
+    assert V.shape == (r, n_in) and U.shape == (n_out, r) and Y.shape == (T, n_out)
+    assert H_save is None or H_save.shape == (T, r)
+    wp, wb = _ws(ws)
+    _check(_lib.lrd_linear_fwd(_ptr(X), _ptr(V), _ptr(U), _ptr(bias), _ptr(Y), _ptr(H_save), T, n_in, n_out, r,
+                               _dt(X), wp, wb, _stream(stream)), "lrd_linear_fwd")
+
+
+def linear_bwd(dY, X, H, V, U, dX, dV, dU, dbias, freeze_mask, ws=None, stream=None):
+    T, n_out = dY.shape
+    r, n_in = V.shape
+    assert U.shape == (n_out, r)
+    wp, wb = _ws(ws)
+    _check(_lib.lrd_linear_bwd(_ptr(dY), _ptr(X), _ptr(H), _ptr(V), _ptr(U), _ptr(dX), _ptr(dV), _ptr(dU),
+                               _ptr(dbias), freeze_mask, T, n_in, n_out, r, _dt(dY), wp, wb, _stream(stream)),
+           "lrd_linear_bwd")
+
+
+def dense_linear_workspace_bytes(T, n_in, n_out, dtype) -> int:
+    return int(_lib.lrd_dense_linear_workspace_bytes(T, n_in, n_out, dtype))
+
+
+def dense_linear_fwd(X, W, bias, Y, ws=None, stream=None):
+    T, n_in = X.shape
+    n_out = W.shape[0]
+    assert W.shape == (n_out, n_in) and Y.shape == (T, n_out)
+    wp, wb = _ws(ws)
+    _check(_lib.lrd_dense_linear_fwd(_ptr(X), _ptr(W), _ptr(bias), _ptr(Y), T, n_in, n_out, _dt(X), wp, wb,
+                                     _stream(stream)), "lrd_dense_linear_fwd")
+
+
+def dense_linear_bwd(dY, X, W, dX, dW, ws=None, stream=None):
+    T, n_out = dY.shape
+    n_in = W.shape[1]
+    wp, wb = _ws(ws)
+    _check(_lib.lrd_dense_linear_bwd(_ptr(dY), _ptr(X), _ptr(W), _ptr(dX), _ptr(dW), T, n_in, n_out, _dt(dY), wp,
+                                     wb, _stream(stream)), "lrd_dense_linear_bwd")
+
+
+# ------------------------------------------------------------------------------- convolutions
+def conv_geom(N, H, W, C, S, r1, r2, k, stride, pad) -> ConvGeom:
+    return ConvGeom(N, H, W, C, S, r1, r2, k, stride, pad)
+
+
+def tucker_conv_workspace_bytes(g: ConvGeom, dtype, freeze_mask=0) -> int:
+    return int(_lib.lrd_tucker_conv_workspace_bytes(ctypes.byref(g), dtype, freeze_mask))
+
+
+def tucker_conv_fwd(X, P1, G, P2, Y, A_save, B_save, g: ConvGeom, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(_lib.lrd_tucker_conv_fwd(_ptr(X), _ptr(P1), _ptr(G), _ptr(P2), _ptr(Y), _ptr(A_save), _ptr(B_save),
+                                    ctypes.byref(g), _dt(X), wp, wb, _stream(stream)), "lrd_tucker_conv_fwd")
+
+
+def tucker_conv_bwd(dY, X, A, B, P1, G, P2, dX, dP1, dG, dP2, freeze_mask, g: ConvGeom, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(_lib.lrd_tucker_conv_bwd(_ptr(dY), _ptr(X), _ptr(A), _ptr(B), _ptr(P1), _ptr(G), _ptr(P2), _ptr(dX),
+                                    _ptr(dP1), _ptr(dG), _ptr(dP2), freeze_mask, ctypes.byref(g), _dt(dY), wp, wb,
+                                    _stream(stream)), "lrd_tucker_conv_bwd")
+
+
+def dense_conv_workspace_bytes(g: ConvGeom, dtype) -> int:
+    return int(_lib.lrd_dense_conv_workspace_bytes(ctypes.byref(g), dtype))
+
+
+def dense_conv_fwd(X, W, Y, g: ConvGeom, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(_lib.lrd_dense_conv_fwd(_ptr(X), _ptr(W), _ptr(Y), ctypes.byref(g), _dt(X), wp, wb, _stream(stream)),
+           "lrd_dense_conv_fwd")
+
+
+def dense_conv_bwd(dY, X, W, dX, dW, g: ConvGeom, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(_lib.lrd_dense_conv_bwd(_ptr(dY), _ptr(X), _ptr(W), _ptr(dX), _ptr(dW), ctypes.byref(g), _dt(dY), wp, wb,
+                                   _stream(stream)), "lrd_dense_conv_bwd")
+
+
+# ------------------------------------------------------------------------------- glue
+def gelu_fwd(Z, A, stream=None):
+    _check(_lib.lrd_gelu_fwd(_ptr(Z), _ptr(A), Z.numel(), _dt(Z), _stream(stream)), "lrd_gelu_fwd")
+
+
+def gelu_bwd(dA, Z, dZ, stream=None):
+    _check(_lib.lrd_gelu_bwd(_ptr(dA), _ptr(Z), _ptr(dZ), Z.numel(), _dt(Z), _stream(stream)), "lrd_gelu_bwd")

@@ -1,0 +1,138 @@
+// Elementwise glue and small reductions: GELU (erf form) forward/backward, column sums for the
+// bias gradient, and the fixed-order sum of split-K partial products.
+#include "lrd_internal.hpp"
+
+namespace lrd {
+namespace {
+
+__device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.f + erff(z * 0.70710678118654752f)); }
+
+__device__ __forceinline__ float gelu_grad_f(float z)
+{
+    float Phi = 0.5f * (1.f + erff(z * 0.70710678118654752f));
+    float phi = 0.39894228040143268f * __expf(-0.5f * z * z);
+    return Phi + z * phi;
+}
+
+// 8 bf16 (16 bytes) per thread per step; n8 = number of whole groups of 8.
+__global__ __launch_bounds__(256) void gelu_fwd_bf16(const bf16_t* __restrict__ Z, bf16_t* __restrict__ A, int64_t n)
+{
+    int64_t n8 = n / 8;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < n8; g += stride) {
+        bf16x8 z = *reinterpret_cast<const bf16x8*>(Z + g * 8);
+        bf16x8 a;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a[e] = (bf16_t)gelu_f((float)z[e]);
+        *reinterpret_cast<bf16x8*>(A + g * 8) = a;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < n - n8 * 8) {
+        int64_t i = n8 * 8 + threadIdx.x;
+        A[i] = (bf16_t)gelu_f((float)Z[i]);
+    }
+}
+
+__global__ __launch_bounds__(256) void gelu_bwd_bf16(const bf16_t* __restrict__ dA, const bf16_t* __restrict__ Z,
+                                                     bf16_t* __restrict__ dZ, int64_t n)
+{
+    int64_t n8 = n / 8;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < n8; g += stride) {
+        bf16x8 z = *reinterpret_cast<const bf16x8*>(Z + g * 8);
+        bf16x8 d = *reinterpret_cast<const bf16x8*>(dA + g * 8);
+        bf16x8 o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = (bf16_t)((float)d[e] * gelu_grad_f((float)z[e]));
+        *reinterpret_cast<bf16x8*>(dZ + g * 8) = o;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < n - n8 * 8) {
+        int64_t i = n8 * 8 + threadIdx.x;
+        dZ[i] = (bf16_t)((float)dA[i] * gelu_grad_f((float)Z[i]));
+    }
+}
+
+__global__ __launch_bounds__(256) void gelu_fwd_f32(const float* __restrict__ Z, float* __restrict__ A, int64_t n)
+{
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) A[i] = gelu_f(Z[i]);
+}
+
+__global__ __launch_bounds__(256) void gelu_bwd_f32(const float* __restrict__ dA, const float* __restrict__ Z,
+                                                    float* __restrict__ dZ, int64_t n)
+{
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+        dZ[i] = dA[i] * gelu_grad_f(Z[i]);
+}
+
+// out[c] = sum_t dY[t][c]; one block per 64 columns, 4 row-lanes per column, fixed order.
+template <class T>
+__global__ __launch_bounds__(256) void column_sums_kernel(const T* __restrict__ dY, float* __restrict__ out,
+                                                          int64_t Tn, int64_t n)
+{
+    __shared__ float part[4][64];
+    int c = threadIdx.x % 64, lane = threadIdx.x / 64;
+    int64_t col = (int64_t)blockIdx.x * 64 + c;
+    float s = 0.f;
+    if (col < n)
+        for (int64_t t = lane; t < Tn; t += 4) s += to_f32(dY[t * n + col]);
+    part[lane][c] = s;
+    __syncthreads();
+    if (lane == 0 && col < n) out[col] = (part[0][c] + part[1][c]) + (part[2][c] + part[3][c]);
+}
+
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, float* __restrict__ C,
+                                                              int64_t ldc, int64_t M, int64_t N, int splits)
+{
+    int64_t total = M * N;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        float s = 0.f;
+        for (int z = 0; z < splits; ++z) s += partial[(int64_t)z * total + i];
+        C[(i / N) * ldc + (i % N)] = s;
+    }
+}
+
+inline unsigned blocks_for(int64_t items)
+{
+    int64_t b = ceil_div(items, 256);
+    if (b < 1) b = 1;
+    if (b > 256 * 16) b = 256 * 16;
+    return (unsigned)b;
+}
+
+}  // namespace
+
+hipError_t gelu_fwd(const void* Z, void* A, int64_t n, bool bf16, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    if (bf16) hipLaunchKernelGGL(gelu_fwd_bf16, dim3(blocks_for(n / 8 + 1)), dim3(256), 0, st, (const bf16_t*)Z, (bf16_t*)A, n);
+    else hipLaunchKernelGGL(gelu_fwd_f32, dim3(blocks_for(n)), dim3(256), 0, st, (const float*)Z, (float*)A, n);
+    return hipGetLastError();
+}
+
+hipError_t gelu_bwd(const void* dA, const void* Z, void* dZ, int64_t n, bool bf16, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    if (bf16) hipLaunchKernelGGL(gelu_bwd_bf16, dim3(blocks_for(n / 8 + 1)), dim3(256), 0, st, (const bf16_t*)dA, (const bf16_t*)Z, (bf16_t*)dZ, n);
+    else hipLaunchKernelGGL(gelu_bwd_f32, dim3(blocks_for(n)), dim3(256), 0, st, (const float*)dA, (const float*)Z, (float*)dZ, n);
+    return hipGetLastError();
+}
+
+hipError_t column_sums(const void* dY, float* out, int64_t T, int64_t n, bool bf16, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    dim3 grid((unsigned)ceil_div(n, 64));
+    if (bf16) hipLaunchKernelGGL(column_sums_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)dY, out, T, n);
+    else hipLaunchKernelGGL(column_sums_kernel<float>, grid, dim3(256), 0, st, (const float*)dY, out, T, n);
+    return hipGetLastError();
+}
+
+hipError_t reduce_partials(const float* partial, float* C, int64_t ldc, int64_t M, int64_t N, int splits,
+                           hipStream_t st)
+{
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks_for(M * N)), dim3(256), 0, st, partial, C, ldc, M, N, splits);
+    return hipGetLastError();
+}
+
+}  // namespace lrd

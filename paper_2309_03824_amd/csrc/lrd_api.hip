@@ -1,0 +1,470 @@
+// C-ABI entry points: argument validation, workspace carving, and the composition of each layer
+// pass out of matrix products (see lrd.h for the contract of every call).
+#include <algorithm>
+
+#include "lrd.h"
+#include "lrd_internal.hpp"
+
+namespace lrd {
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round256(size_t b) { return (b + 255) & ~size_t(255); }
+inline size_t esize(lrd_dtype dt) { return dt == LRD_BF16 ? 2 : 4; }
+inline bool dtype_ok(lrd_dtype dt) { return dt == LRD_F32 || dt == LRD_BF16; }
+
+// Bump allocator over the caller's workspace.
+struct Carver {
+    char* base;
+    size_t cap, used = 0;
+    bool ok = true;
+    Carver(void* p, size_t n) : base((char*)p), cap(n) {}
+    void* take(size_t bytes)
+    {
+        size_t b = round256(bytes);
+        if (!base || used + b > cap) { ok = false; return nullptr; }
+        void* p = base + used;
+        used += b;
+        return p;
+    }
+};
+
+#define LRD_TRY(expr)                                   \
+    do {                                                \
+        hipError_t e__ = (expr);                        \
+        if (e__ != hipSuccess) return LRD_ERR_RUNTIME;  \
+    } while (0)
+
+// C[M x N] = A[M x K] . B^T with row-major operands A [M x K], B [N x K].
+MatOp nt(const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, int64_t M,
+         int64_t N, int64_t K, lrd_dtype dt, bool out_f32)
+{
+    MatOp op;
+    op.A = A; op.a_sm = lda; op.a_sk = 1;
+    op.B = B; op.b_sn = ldb; op.b_sk = 1;
+    op.C = C; op.ldc = ldc;
+    op.M = M; op.N = N; op.K = K;
+    op.in_bf16 = dt == LRD_BF16;
+    op.out_f32 = out_f32 || dt == LRD_F32;
+    return op;
+}
+
+// C[M x N] = A[M x K] . B with row-major B [K x N].
+MatOp nn(const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, int64_t M,
+         int64_t N, int64_t K, lrd_dtype dt)
+{
+    MatOp op = nt(A, lda, B, 0, C, ldc, M, N, K, dt, false);
+    op.b_sn = 1; op.b_sk = ldb;
+    return op;
+}
+
+// C[M x N] (fp32) = A^T . B with row-major A [K x M], B [K x N]: the weight-gradient shape.
+MatOp tn(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int64_t ldc, int64_t M,
+         int64_t N, int64_t K, lrd_dtype dt)
+{
+    MatOp op = nt(A, 0, B, 0, C, ldc, M, N, K, dt, true);
+    op.a_sm = 1; op.a_sk = lda;
+    op.b_sn = 1; op.b_sk = ldb;
+    return op;
+}
+
+size_t partial_bytes(int64_t M, int64_t N, int64_t K, lrd_dtype dt)
+{
+    int s = choose_splits(M, N, K, dt == LRD_BF16);
+    return s > 1 ? round256((size_t)s * (size_t)M * (size_t)N * sizeof(float)) : 0;
+}
+
+void attach_splits(MatOp& op, Carver& cv, lrd_dtype dt)
+{
+    int s = choose_splits(op.M, op.N, op.K, dt == LRD_BF16);
+    if (s > 1) {
+        op.partial = (float*)cv.take((size_t)s * (size_t)op.M * (size_t)op.N * sizeof(float));
+        op.splits = op.partial ? s : 1;
+    }
+}
+
+bool linear_dims_ok(int64_t T, int64_t in, int64_t out, int64_t r)
+{
+    return T >= 1 && in >= 1 && out >= 1 && r >= 1 && r <= std::min(in, out) &&
+           T < (int64_t(1) << 31) && in < (int64_t(1) << 24) && out < (int64_t(1) << 24);
+}
+
+ConvShape core_shape(const lrd_conv_geom& g, int64_t I, int64_t O)
+{
+    ConvShape cs;
+    cs.N = (int)g.N; cs.H = (int)g.H; cs.W = (int)g.W;
+    cs.Ho = (int)((g.H + 2 * g.pad - g.k) / g.stride + 1);
+    cs.Wo = (int)((g.W + 2 * g.pad - g.k) / g.stride + 1);
+    cs.I = (int)I; cs.O = (int)O;
+    cs.k = g.k; cs.stride = g.stride; cs.pad = g.pad;
+    return cs;
+}
+
+bool geom_ok(const lrd_conv_geom* g, bool tucker)
+{
+    if (!g) return false;
+    if (g->N < 1 || g->H < 1 || g->W < 1 || g->C < 1 || g->S < 1) return false;
+    if (g->k < 1 || g->stride < 1 || g->pad < 0) return false;
+    if (g->H + 2 * g->pad < g->k || g->W + 2 * g->pad < g->k) return false;
+    if (tucker && (g->r1 < 1 || g->r1 > g->C || g->r2 < 1 || g->r2 > g->S)) return false;
+    const int64_t lim = int64_t(1) << 31;
+    int64_t widest = std::max(std::max(g->C, g->S), std::max(g->r1, g->r2));
+    if (g->N * g->H * g->W >= lim / std::max<int64_t>(widest, 1)) return false;  // 32-bit pixel*channel index space
+    return true;
+}
+
+}  // namespace
+}  // namespace lrd
+
+using namespace lrd;
+
+extern "C" {
+
+// ------------------------------------------------------------------------------------ linear
+size_t lrd_linear_workspace_bytes(int64_t T, int64_t in, int64_t out, int64_t r, lrd_dtype dt,
+                                  uint32_t freeze_mask)
+{
+    (void)freeze_mask;
+    if (!dtype_ok(dt) || !linear_dims_ok(T, in, out, r)) return 0;
+    size_t act = round256((size_t)T * (size_t)r * esize(dt));
+    // forward: H when not side-stored; backward: dH, a recomputed H, and split-K partials
+    size_t bwd = 2 * act + partial_bytes(out, r, T, dt) + partial_bytes(r, in, T, dt);
+    return std::max(act, bwd);
+}
+
+lrd_status lrd_linear_fwd(const void* X, const void* V, const void* U, const float* bias, void* Y,
+                          void* H_save, int64_t T, int64_t in, int64_t out, int64_t r,
+                          lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    if (!dtype_ok(dt) || !linear_dims_ok(T, in, out, r) || !X || !V || !U || !Y) return LRD_ERR_INVALID_ARG;
+    if (!aligned16(X) || !aligned16(V) || !aligned16(U) || !aligned16(Y) || !aligned16(H_save) || !aligned16(ws) ||
+        !aligned16(bias))
+        return LRD_ERR_ALIGNMENT;
+    hipStream_t st = (hipStream_t)hip_stream;
+
+    if (dt == LRD_BF16) {
+        ChainOp ch;
+        ch.A = X; ch.lda = in;
+        ch.B1 = V; ch.b1_sn = in; ch.b1_sk = 1;
+        ch.B2 = U; ch.b2_sn = r; ch.b2_sk = 1;
+        ch.C = Y; ch.ldc = out;
+        ch.mid_save = H_save; ch.ldmid = r;
+        ch.bias = bias;
+        ch.M = T; ch.K1 = in; ch.R = r; ch.N2 = out;
+        if (mfma_chain_supported(ch)) {
+            LRD_TRY(mfma_chain(ch, st));
+            return LRD_OK;
+        }
+    }
+    Carver cv(ws, ws_bytes);
+    void* H = H_save ? H_save : cv.take((size_t)T * r * esize(dt));
+    if (!H) return LRD_ERR_WORKSPACE;
+    MatOp g1 = nt(X, in, V, in, H, r, T, r, in, dt, false);
+    MatOp g2 = nt(H, r, U, r, Y, out, T, out, r, dt, false);
+    g2.bias = bias;
+    LRD_TRY(run_matop(g1, st));
+    LRD_TRY(run_matop(g2, st));
+    return LRD_OK;
+}
+
+lrd_status lrd_linear_bwd(const void* dY, const void* X, const void* H, const void* V,
+                          const void* U, void* dX, float* dV, float* dU, float* dbias,
+                          uint32_t freeze_mask, int64_t T, int64_t in, int64_t out, int64_t r,
+                          lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    if (!dtype_ok(dt) || !linear_dims_ok(T, in, out, r) || !dY || !V || !U) return LRD_ERR_INVALID_ARG;
+    if (freeze_mask & ~uint32_t(LRD_FREEZE_L0 | LRD_FREEZE_L1)) return LRD_ERR_INVALID_ARG;
+    const bool train_v = !(freeze_mask & LRD_FREEZE_L0), train_u = !(freeze_mask & LRD_FREEZE_L1);
+    if (train_v && (!dV || !X)) return LRD_ERR_INVALID_ARG;
+    if (train_u && (!dU || (!H && !X))) return LRD_ERR_INVALID_ARG;
+    if (!aligned16(dY) || !aligned16(X) || !aligned16(H) || !aligned16(V) || !aligned16(U) || !aligned16(dX) ||
+        !aligned16(ws) || (train_v && !aligned16(dV)) || (train_u && !aligned16(dU)) || !aligned16(dbias))
+        return LRD_ERR_ALIGNMENT;
+    hipStream_t st = (hipStream_t)hip_stream;
+    Carver cv(ws, ws_bytes);
+    const size_t act = (size_t)T * r * esize(dt);
+    const bool need_dH = dX || train_v;
+
+    // Carve everything first so that a short workspace is reported before any launch.
+    void* dH = need_dH ? cv.take(act) : nullptr;
+    void* Hre = (train_u && !H) ? cv.take(act) : nullptr;
+    MatOp wu, wv;
+    if (train_u) {
+        wu = tn(dY, out, H ? H : Hre, r, dU, r, out, r, T, dt);
+        attach_splits(wu, cv, dt);
+    }
+    if (train_v) {
+        wv = tn(dH, r, X, in, dV, in, r, in, T, dt);
+        // the two weight-gradient products run one after the other and may share partials
+        if (train_u && wu.partial) {
+            int s = choose_splits(wv.M, wv.N, wv.K, dt == LRD_BF16);
+            size_t need = (size_t)s * wv.M * wv.N * sizeof(float), have = round256((size_t)wu.splits * wu.M * wu.N * sizeof(float));
+            if (s > 1 && need <= have) { wv.partial = wu.partial; wv.splits = s; }
+            else attach_splits(wv, cv, dt);
+        } else {
+            attach_splits(wv, cv, dt);
+        }
+    }
+    if (!cv.ok) return LRD_ERR_WORKSPACE;
+
+    if (need_dH) {
+        bool fused = false;
+        if (dt == LRD_BF16 && dX) {
+            ChainOp ch;
+            ch.A = dY; ch.lda = out;
+            ch.B1 = U; ch.b1_sn = 1; ch.b1_sk = r;     // B1(j, o) = U[o][j]
+            ch.B2 = V; ch.b2_sn = 1; ch.b2_sk = in;    // B2(i, j) = V[j][i]
+            ch.C = dX; ch.ldc = in;
+            ch.mid_save = train_v ? dH : nullptr; ch.ldmid = r;
+            ch.M = T; ch.K1 = out; ch.R = r; ch.N2 = in;
+            if (mfma_chain_supported(ch)) {
+                LRD_TRY(mfma_chain(ch, st));
+                fused = true;
+            }
+        }
+        if (!fused) {
+            LRD_TRY(run_matop(nn(dY, out, U, r, dH, r, T, r, out, dt), st));
+            if (dX) LRD_TRY(run_matop(nn(dH, r, V, in, dX, in, T, in, r, dt), st));
+        }
+    }
+    if (train_u) {
+        if (!H) LRD_TRY(run_matop(nt(X, in, V, in, Hre, r, T, r, in, dt, false), st));
+        LRD_TRY(run_matop(wu, st));
+    }
+    if (train_v) LRD_TRY(run_matop(wv, st));
+    if (dbias) LRD_TRY(column_sums(dY, dbias, T, out, dt == LRD_BF16, st));
+    return LRD_OK;
+}
+
+// ------------------------------------------------------------------------------------ dense linear
+size_t lrd_dense_linear_workspace_bytes(int64_t T, int64_t in, int64_t out, lrd_dtype dt)
+{
+    if (!dtype_ok(dt) || T < 1 || in < 1 || out < 1) return 0;
+    return partial_bytes(out, in, T, dt);
+}
+
+lrd_status lrd_dense_linear_fwd(const void* X, const void* W, const float* bias, void* Y, int64_t T,
+                                int64_t in, int64_t out, lrd_dtype dt, void* ws, size_t ws_bytes,
+                                void* hip_stream)
+{
+    (void)ws; (void)ws_bytes;
+    if (!dtype_ok(dt) || !linear_dims_ok(T, in, out, 1) || !X || !W || !Y) return LRD_ERR_INVALID_ARG;
+    if (!aligned16(X) || !aligned16(W) || !aligned16(Y) || !aligned16(bias)) return LRD_ERR_ALIGNMENT;
+    MatOp g = nt(X, in, W, in, Y, out, T, out, in, dt, false);
+    g.bias = bias;
+    LRD_TRY(run_matop(g, (hipStream_t)hip_stream));
+    return LRD_OK;
+}
+
+lrd_status lrd_dense_linear_bwd(const void* dY, const void* X, const void* W, void* dX, float* dW,
+                                int64_t T, int64_t in, int64_t out, lrd_dtype dt, void* ws,
+                                size_t ws_bytes, void* hip_stream)
+{
+    if (!dtype_ok(dt) || !linear_dims_ok(T, in, out, 1) || !dY || !W || (dW && !X)) return LRD_ERR_INVALID_ARG;
+    if (!aligned16(dY) || !aligned16(X) || !aligned16(W) || !aligned16(dX) || !aligned16(dW) || !aligned16(ws))
+        return LRD_ERR_ALIGNMENT;
+    hipStream_t st = (hipStream_t)hip_stream;
+    Carver cv(ws, ws_bytes);
+    MatOp wg;
+    if (dW) {
+        wg = tn(dY, out, X, in, dW, in, out, in, T, dt);
+        attach_splits(wg, cv, dt);
+        if (!cv.ok) return LRD_ERR_WORKSPACE;
+    }
+    if (dX) LRD_TRY(run_matop(nn(dY, out, W, in, dX, in, T, in, out, dt), st));
+    if (dW) LRD_TRY(run_matop(wg, st));
+    return LRD_OK;
+}
+
+// ------------------------------------------------------------------------------------ Tucker conv
+size_t lrd_tucker_conv_workspace_bytes(const lrd_conv_geom* g, lrd_dtype dt, uint32_t freeze_mask)
+{
+    (void)freeze_mask;
+    if (!dtype_ok(dt) || !geom_ok(g, true)) return 0;
+    ConvShape cs = core_shape(*g, g->r1, g->r2);
+    size_t pin = (size_t)g->N * g->H * g->W, pout = (size_t)g->N * cs.Ho * cs.Wo;
+    size_t a = round256(pin * g->r1 * esize(dt)), b = round256(pout * g->r2 * esize(dt));
+    size_t kk = (size_t)g->k * g->k;
+    size_t part = std::max(std::max(partial_bytes(g->S, g->r2, pout, dt), partial_bytes(g->r2, kk * g->r1, pout, dt)),
+                           partial_bytes(g->r1, g->C, pin, dt));
+    // forward: A and B when not side-stored; backward: dA, dB, recomputed A and B, partials
+    return 2 * (a + b) + part;
+}
+
+lrd_status lrd_tucker_conv_fwd(const void* X, const void* P1, const void* G, const void* P2,
+                               void* Y, void* A_save, void* B_save, const lrd_conv_geom* g,
+                               lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    if (!dtype_ok(dt) || !geom_ok(g, true) || !X || !P1 || !G || !P2 || !Y) return LRD_ERR_INVALID_ARG;
+    if (!aligned16(X) || !aligned16(P1) || !aligned16(G) || !aligned16(P2) || !aligned16(Y) || !aligned16(A_save) ||
+        !aligned16(B_save) || !aligned16(ws))
+        return LRD_ERR_ALIGNMENT;
+    hipStream_t st = (hipStream_t)hip_stream;
+    ConvShape cs = core_shape(*g, g->r1, g->r2);
+    const int64_t pin = g->N * g->H * g->W, pout = g->N * (int64_t)cs.Ho * cs.Wo;
+    const int64_t kk = (int64_t)g->k * g->k;
+    Carver cv(ws, ws_bytes);
+    void* A = A_save ? A_save : cv.take((size_t)pin * g->r1 * esize(dt));
+    void* B = B_save ? B_save : cv.take((size_t)pout * g->r2 * esize(dt));
+    if (!A || !B) return LRD_ERR_WORKSPACE;
+
+    LRD_TRY(run_matop(nt(X, g->C, P1, g->C, A, g->r1, pin, g->r1, g->C, dt, false), st));
+    MatOp core = nt(A, g->r1, G, kk * g->r1, B, g->r2, pout, g->r2, kk * g->r1, dt, false);
+    core.gather = GATHER_CONV_FWD;
+    core.cs = cs;
+    LRD_TRY(run_matop(core, st));
+    LRD_TRY(run_matop(nt(B, g->r2, P2, g->r2, Y, g->S, pout, g->S, g->r2, dt, false), st));
+    return LRD_OK;
+}
+
+lrd_status lrd_tucker_conv_bwd(const void* dY, const void* X, const void* A, const void* B,
+                               const void* P1, const void* G, const void* P2, void* dX,
+                               float* dP1, float* dG, float* dP2, uint32_t freeze_mask,
+                               const lrd_conv_geom* g, lrd_dtype dt, void* ws, size_t ws_bytes,
+                               void* hip_stream)
+{
+    if (!dtype_ok(dt) || !geom_ok(g, true) || !dY || !P1 || !G || !P2) return LRD_ERR_INVALID_ARG;
+    if (freeze_mask & ~uint32_t(LRD_FREEZE_L0 | LRD_FREEZE_L1 | LRD_FREEZE_L2)) return LRD_ERR_INVALID_ARG;
+    const bool t1 = !(freeze_mask & LRD_FREEZE_L0), tg = !(freeze_mask & LRD_FREEZE_L1),
+               t2 = !(freeze_mask & LRD_FREEZE_L2);
+    if ((t1 && (!dP1 || !X)) || (tg && !dG) || (t2 && !dP2)) return LRD_ERR_INVALID_ARG;
+    const bool need_A = tg || (t2 && !B);            // A feeds dG, and B's recomputation
+    if (((need_A && !A) || (t2 && !B)) && !X) return LRD_ERR_INVALID_ARG;
+    if (!aligned16(dY) || !aligned16(X) || !aligned16(A) || !aligned16(B) || !aligned16(P1) || !aligned16(G) ||
+        !aligned16(P2) || !aligned16(dX) || !aligned16(ws) || (t1 && !aligned16(dP1)) || (tg && !aligned16(dG)) ||
+        (t2 && !aligned16(dP2)))
+        return LRD_ERR_ALIGNMENT;
+    hipStream_t st = (hipStream_t)hip_stream;
+    ConvShape cs = core_shape(*g, g->r1, g->r2);
+    const int64_t pin = g->N * g->H * g->W, pout = g->N * (int64_t)cs.Ho * cs.Wo;
+    const int64_t kk = (int64_t)g->k * g->k;
+    const int64_t r1 = g->r1, r2 = g->r2, C = g->C, S = g->S;
+    Carver cv(ws, ws_bytes);
+    const bool need_dA = dX || t1;
+    const bool need_dB = need_dA || tg;
+
+    void* dB = need_dB ? cv.take((size_t)pout * r2 * esize(dt)) : nullptr;
+    void* dA = need_dA ? cv.take((size_t)pin * r1 * esize(dt)) : nullptr;
+    void* Are = (need_A && !A) ? cv.take((size_t)pin * r1 * esize(dt)) : nullptr;
+    void* Bre = (t2 && !B) ? cv.take((size_t)pout * r2 * esize(dt)) : nullptr;
+    const void* Ause = A ? A : Are;
+    const void* Buse = B ? B : Bre;
+    MatOp w2, wg, w1;
+    float* shared_partial = nullptr;
+    size_t shared_bytes = 0;
+    auto splits_for = [&](MatOp& op) {
+        int s = choose_splits(op.M, op.N, op.K, dt == LRD_BF16);
+        if (s <= 1) return;
+        size_t need = (size_t)s * op.M * op.N * sizeof(float);
+        if (need > shared_bytes) return;
+        op.partial = shared_partial; op.splits = s;
+    };
+    if (t2) w2 = tn(dY, S, Buse, r2, dP2, r2, S, r2, pout, dt);
+    if (tg) {
+        wg = tn(dB, r2, Ause, r1, dG, kk * r1, r2, kk * r1, pout, dt);
+        wg.gather = GATHER_CONV_WGRAD;
+        wg.cs = cs;
+    }
+    if (t1) w1 = tn(dA, r1, X, C, dP1, C, r1, C, pin, dt);
+    // one partial buffer, sized for the largest of the three products, used by them in turn
+    shared_bytes = std::max(std::max(t2 ? partial_bytes(S, r2, pout, dt) : 0, tg ? partial_bytes(r2, kk * r1, pout, dt) : 0),
+                            t1 ? partial_bytes(r1, C, pin, dt) : 0);
+    if (shared_bytes) shared_partial = (float*)cv.take(shared_bytes);
+    if (!cv.ok) return LRD_ERR_WORKSPACE;
+    if (t2) splits_for(w2);
+    if (tg) splits_for(wg);
+    if (t1) splits_for(w1);
+
+    if (need_dB) LRD_TRY(run_matop(nn(dY, S, P2, r2, dB, r2, pout, r2, S, dt), st));
+    if (need_dA) {
+        MatOp dg = nt(dB, r2, G, 0, dA, r1, pin, r1, kk * r2, dt, false);
+        dg.gather = GATHER_CONV_DGRAD;
+        dg.cs = cs;
+        LRD_TRY(run_matop(dg, st));
+    }
+    if (dX) LRD_TRY(run_matop(nn(dA, r1, P1, C, dX, C, pin, C, r1, dt), st));
+    if (Are) LRD_TRY(run_matop(nt(X, C, P1, C, Are, r1, pin, r1, C, dt, false), st));
+    if (Bre) {
+        MatOp core = nt(Ause, r1, G, kk * r1, Bre, r2, pout, r2, kk * r1, dt, false);
+        core.gather = GATHER_CONV_FWD;
+        core.cs = cs;
+        LRD_TRY(run_matop(core, st));
+    }
+    if (t2) LRD_TRY(run_matop(w2, st));
+    if (tg) LRD_TRY(run_matop(wg, st));
+    if (t1) LRD_TRY(run_matop(w1, st));
+    return LRD_OK;
+}
+
+// ------------------------------------------------------------------------------------ dense conv
+size_t lrd_dense_conv_workspace_bytes(const lrd_conv_geom* g, lrd_dtype dt)
+{
+    if (!dtype_ok(dt) || !geom_ok(g, false)) return 0;
+    ConvShape cs = core_shape(*g, g->C, g->S);
+    return partial_bytes(g->S, (int64_t)g->k * g->k * g->C, g->N * (int64_t)cs.Ho * cs.Wo, dt);
+}
+
+lrd_status lrd_dense_conv_fwd(const void* X, const void* W, void* Y, const lrd_conv_geom* g,
+                              lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    (void)ws; (void)ws_bytes;
+    if (!dtype_ok(dt) || !geom_ok(g, false) || !X || !W || !Y) return LRD_ERR_INVALID_ARG;
+    if (!aligned16(X) || !aligned16(W) || !aligned16(Y)) return LRD_ERR_ALIGNMENT;
+    ConvShape cs = core_shape(*g, g->C, g->S);
+    const int64_t pout = g->N * (int64_t)cs.Ho * cs.Wo, K = (int64_t)g->k * g->k * g->C;
+    MatOp op = nt(X, g->C, W, K, Y, g->S, pout, g->S, K, dt, false);
+    op.gather = GATHER_CONV_FWD;
+    op.cs = cs;
+    LRD_TRY(run_matop(op, (hipStream_t)hip_stream));
+    return LRD_OK;
+}
+
+lrd_status lrd_dense_conv_bwd(const void* dY, const void* X, const void* W, void* dX, float* dW,
+                              const lrd_conv_geom* g, lrd_dtype dt, void* ws, size_t ws_bytes,
+                              void* hip_stream)
+{
+    if (!dtype_ok(dt) || !geom_ok(g, false) || !dY || !W || (dW && !X)) return LRD_ERR_INVALID_ARG;
+    if (!aligned16(dY) || !aligned16(X) || !aligned16(W) || !aligned16(dX) || !aligned16(dW) || !aligned16(ws))
+        return LRD_ERR_ALIGNMENT;
+    hipStream_t st = (hipStream_t)hip_stream;
+    ConvShape cs = core_shape(*g, g->C, g->S);
+    const int64_t pin = g->N * g->H * g->W, pout = g->N * (int64_t)cs.Ho * cs.Wo;
+    const int64_t kk = (int64_t)g->k * g->k;
+    Carver cv(ws, ws_bytes);
+    MatOp wg;
+    if (dW) {
+        wg = tn(dY, g->S, X, g->C, dW, kk * g->C, g->S, kk * g->C, pout, dt);
+        wg.gather = GATHER_CONV_WGRAD;
+        wg.cs = cs;
+        attach_splits(wg, cv, dt);
+        if (!cv.ok) return LRD_ERR_WORKSPACE;
+    }
+    if (dX) {
+        MatOp dg = nt(dY, g->S, W, 0, dX, g->C, pin, g->C, kk * g->S, dt, false);
+        dg.gather = GATHER_CONV_DGRAD;
+        dg.cs = cs;
+        LRD_TRY(run_matop(dg, st));
+    }
+    if (dW) LRD_TRY(run_matop(wg, st));
+    return LRD_OK;
+}
+
+// ------------------------------------------------------------------------------------ glue
+lrd_status lrd_gelu_fwd(const void* Z, void* A, int64_t n, lrd_dtype dt, void* hip_stream)
+{
+    if (!dtype_ok(dt) || n < 0 || !Z || !A) return LRD_ERR_INVALID_ARG;
+    if (!aligned16(Z) || !aligned16(A)) return LRD_ERR_ALIGNMENT;
+    LRD_TRY(gelu_fwd(Z, A, n, dt == LRD_BF16, (hipStream_t)hip_stream));
+    return LRD_OK;
+}
+
+lrd_status lrd_gelu_bwd(const void* dA, const void* Z, void* dZ, int64_t n, lrd_dtype dt,
+                        void* hip_stream)
+{
+    if (!dtype_ok(dt) || n < 0 || !dA || !Z || !dZ) return LRD_ERR_INVALID_ARG;
+    if (!aligned16(dA) || !aligned16(Z) || !aligned16(dZ)) return LRD_ERR_ALIGNMENT;
+    LRD_TRY(gelu_bwd(dA, Z, dZ, n, dt == LRD_BF16, (hipStream_t)hip_stream));
+    return LRD_OK;
+}
+
+}  // extern "C"

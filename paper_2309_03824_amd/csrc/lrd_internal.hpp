@@ -1,0 +1,70 @@
+// Internal (C++) interface between the C-ABI entry points and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "lrd_device.hpp"
+
+namespace lrd {
+
+enum Gather : int {
+    GATHER_NONE = 0,
+    GATHER_CONV_FWD = 1,    // A rows are output pixels, K runs over (u,v,i) taps of an NHWC input
+    GATHER_CONV_DGRAD = 2,  // A rows are input pixels, K runs over (u,v,o); B is W[o,u,v,i] read as (i | u,v,o)
+    GATHER_CONV_WGRAD = 3   // B rows are taps (u,v,i), K runs over output pixels
+};
+
+// One product  C[M x N] = A[M x K] . B[N x K]^T (+ bias[n]),  fp32 accumulation.
+// A(m,k) = A[m*a_sm + k*a_sk], B(n,k) = B[n*b_sn + k*b_sk] (element strides) unless a gather mode
+// replaces the addressing of one operand by a convolution's tap geometry.
+struct MatOp {
+    const void* A = nullptr;
+    int64_t a_sm = 0, a_sk = 0;
+    const void* B = nullptr;
+    int64_t b_sn = 0, b_sk = 0;
+    void* C = nullptr;
+    int64_t ldc = 0;
+    const float* bias = nullptr;
+    int64_t M = 0, N = 0, K = 0;
+    bool in_bf16 = false;   // operands are bf16 (else fp32)
+    bool out_f32 = true;    // C is fp32 (else the operand dtype)
+    int gather = GATHER_NONE;
+    ConvShape cs{};
+    // Split-K: when splits > 1, slice z of K writes partial[z][M][N] (fp32) and a second kernel
+    // sums the slices in a fixed order into C, so results do not depend on scheduling.
+    int splits = 1;
+    float* partial = nullptr;
+};
+
+// Engines.  Each returns hipSuccess or the launch error.
+hipError_t generic_matop(const MatOp& op, hipStream_t st);          // any MatOp, plain FMA tiles
+bool mfma_matop_supported(const MatOp& op);                         // bf16 MFMA engine covers it?
+hipError_t mfma_matop(const MatOp& op, hipStream_t st);
+hipError_t run_matop(const MatOp& op, hipStream_t st);              // picks an engine
+
+// Workspace floats a MatOp of this shape needs for split-K (0 if it will not be split).
+int choose_splits(int64_t M, int64_t N, int64_t K, bool in_bf16);
+
+// Fused pair  C2[M x N2] = (A[M x K1] . B1[R x K1]^T) . B2[N2 x R]^T : the rank-R intermediate
+// stays on chip; optionally it is also stored (mid_save, [M x R], operand dtype).
+struct ChainOp {
+    const void* A = nullptr;  int64_t lda = 0;            // [M x K1], K-contiguous
+    const void* B1 = nullptr; int64_t b1_sn = 0, b1_sk = 0;  // B1(j,k)
+    const void* B2 = nullptr; int64_t b2_sn = 0, b2_sk = 0;  // B2(n,j)
+    void* C = nullptr; int64_t ldc = 0;
+    void* mid_save = nullptr; int64_t ldmid = 0;
+    const float* bias = nullptr;
+    int64_t M = 0, K1 = 0, R = 0, N2 = 0;
+};
+bool mfma_chain_supported(const ChainOp& op);
+hipError_t mfma_chain(const ChainOp& op, hipStream_t st);
+
+// Elementwise / reductions.
+hipError_t gelu_fwd(const void* Z, void* A, int64_t n, bool bf16, hipStream_t st);
+hipError_t gelu_bwd(const void* dA, const void* Z, void* dZ, int64_t n, bool bf16, hipStream_t st);
+hipError_t column_sums(const void* dY, float* out, int64_t T, int64_t n, bool bf16, hipStream_t st);
+hipError_t reduce_partials(const float* partial, float* C, int64_t ldc, int64_t M, int64_t N,
+                           int splits, hipStream_t st);
+
+}  // namespace lrd

@@ -1,0 +1,119 @@
+"""GPU parity: Tucker-2-decomposed convolution (1x1 -> kxk core -> 1x1) forward/backward with
+freezing, and the undecomposed convolution, through the C ABI against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as si
+from parity import check, code, dev, empty, f32, host, seen, workspace
+from paper_2309_03824_amd import binding as lrd
+
+pytestmark = pytest.mark.gpu
+
+SENT = 4321.25
+
+
+def run_tucker(N, Hh, Ww, C, S, r1, r2, k, stride, pad, dt, mask, seed, save=True, want_dx=True, factors=None):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    X = si.gaussian((N, Hh, Ww, C), rng)
+    P1, G, P2 = si.direct_tucker_factors(S, C, k, r1, r2, rng) if factors is None else factors
+    g = lrd.conv_geom(N, Hh, Ww, C, S, r1, r2, k, stride, pad)
+    Ho, Wo = g.out_hw()
+    dY = si.gaussian((N, Ho, Wo, S), rng)
+
+    X_, P1_, G_, P2_, dY_ = dev(X, dt), dev(P1, dt), dev(G, dt), dev(P2, dt), dev(dY, dt)
+    Y_ = empty((N, Ho, Wo, S), dt)
+    A_ = empty((N, Hh, Ww, r1), dt) if save else None
+    B_ = empty((N, Ho, Wo, r2), dt) if save else None
+    ws = workspace(lrd.tucker_conv_workspace_bytes(g, code(dt), mask))
+    lrd.tucker_conv_fwd(X_, P1_, G_, P2_, Y_, A_, B_, g, ws)
+    gX = empty((N, Hh, Ww, C), dt) if want_dx else None
+    g1, gG, g2 = f32((r1, C), SENT), f32((r2, k, k, r1), SENT), f32((S, r2), SENT)
+    lrd.tucker_conv_bwd(dY_, X_, A_, B_, P1_, G_, P2_, gX, g1, gG, g2, mask, g, ws)
+    torch.cuda.synchronize()
+
+    Xo, P1o, Go, P2o, dYo = (seen(a, dt) for a in (X, P1, G, P2, dY))
+    Ao, Bo, Yo = oracle.tucker_fwd(Xo, P1o, Go, P2o, stride, pad)
+    check(host(Y_), Yo, dt, "Y")
+    if save:
+        check(host(A_), Ao, dt, "A")
+        check(host(B_), Bo, dt, "B")
+    go = oracle.tucker_bwd(dYo, Xo, Ao, Bo, P1o, Go, P2o, mask, stride, pad, want_dX=want_dx)
+    if want_dx:
+        check(host(gX), go["dX"], dt, "dX")
+    for bit, (name, t) in enumerate((("dP1", g1), ("dG", gG), ("dP2", g2))):
+        if mask & (1 << bit):
+            assert torch.all(t == SENT), f"frozen {name} was written"
+        else:
+            check(host(t), go[name], dt, name)
+    return dict(Y=Y_, dX=gX, dP1=g1, dG=gG, dP2=g2)
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_small_tucker_all_masks(dt):
+    for mask in range(8):
+        run_tucker(2, 9, 7, 24, 40, 8, 16, 3, 1, 1, dt, mask, seed=mask)
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+@pytest.mark.parametrize("geo", [
+    (1, 12, 12, 16, 16, 5, 7, 3, 2, 1),      # stride 2, raw ranks
+    (3, 8, 10, 32, 24, 16, 8, 1, 1, 0),      # 1x1 core
+    (2, 11, 9, 20, 12, 12, 12, 5, 1, 2),     # 5x5 core
+    (1, 7, 7, 8, 8, 8, 8, 3, 1, 0),          # no padding, full ranks
+    (1, 3, 3, 4, 4, 2, 2, 3, 1, 1),          # image as small as the kernel
+])
+def test_tucker_geometries(dt, geo):
+    run_tucker(*geo, dt, 0, seed=sum(geo))
+    run_tucker(*geo, dt, lrd.freeze_mask(lrd.KIND_TUCKER, 1), seed=sum(geo) + 1)
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_tucker_nullable_arguments(dt):
+    run_tucker(2, 8, 8, 16, 16, 8, 8, 3, 1, 1, dt, 0, seed=1, save=False)
+    run_tucker(2, 8, 8, 16, 16, 8, 8, 3, 1, 1, dt, 0b101, seed=2, save=False, want_dx=False)
+    run_tucker(2, 8, 8, 16, 16, 8, 8, 3, 1, 1, dt, 0b010, seed=3, want_dx=False)
+
+
+def test_resnet_stage_shapes_bf16():
+    """The four 3x3 stage shapes (C = 64/128/256/512 at 56/28/14/7 pixels, ranks C/2 quantized to
+    multiples of 32, stride 1 pad 1), two images each, core frozen (odd epoch of Algorithm 2) and
+    the 1x1 layers frozen (even epoch); Tucker factors from an HOSVD of W ~ N(0, 1/(9C))."""
+    from paper_2309_03824_amd import factorize
+    for stage, (C, hw) in enumerate(((64, 56), (128, 28), (256, 14), (512, 7))):
+        r = lrd.quantize_rank(C // 2, 32)
+        assert r == C // 2
+        W = si.conv_weight(C, C, 3, si.rng_for(4, stage))
+        factors = factorize.tucker2_factors(W, r, r)
+        for epoch in (1, 0):
+            run_tucker(2, hw, hw, C, C, r, r, 3, 1, 1, "bf16", lrd.freeze_mask(lrd.KIND_TUCKER, epoch),
+                       seed=50 + stage, factors=factors)
+
+
+def test_tucker_rank_cliff_shapes_bf16():
+    """Ranks one off a tile boundary (the 257 -> 256 situation of Section 2.1) must stay correct."""
+    for r in (31, 33, 65, 127):
+        run_tucker(1, 14, 14, 160, 136, r, r, 3, 1, 1, "bf16", 0, seed=r)
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_dense_conv(dt):
+    for (N, Hh, Ww, C, S, k, stride, pad) in ((2, 9, 7, 24, 40, 3, 1, 1), (1, 12, 12, 16, 8, 3, 2, 1),
+                                              (2, 14, 14, 64, 64, 3, 1, 1), (1, 6, 6, 5, 3, 5, 1, 2)):
+        rng = np.random.Generator(np.random.PCG64(N * 1000 + C))
+        X, W = si.gaussian((N, Hh, Ww, C), rng), si.conv_weight(S, C, k, rng)
+        g = lrd.conv_geom(N, Hh, Ww, C, S, 1, 1, k, stride, pad)
+        Ho, Wo = g.out_hw()
+        dY = si.gaussian((N, Ho, Wo, S), rng)
+        X_, W_, dY_ = dev(X, dt), dev(W, dt), dev(dY, dt)
+        Y_ = empty((N, Ho, Wo, S), dt)
+        ws = workspace(lrd.dense_conv_workspace_bytes(g, code(dt)))
+        lrd.dense_conv_fwd(X_, W_, Y_, g, ws)
+        gX, gW = empty((N, Hh, Ww, C), dt), f32((S, k, k, C))
+        lrd.dense_conv_bwd(dY_, X_, W_, gX, gW, g, ws)
+        torch.cuda.synchronize()
+        Xo, Wo_, dYo = seen(X, dt), seen(W, dt), seen(dY, dt)
+        check(host(Y_), oracle.conv_fwd(Xo, Wo_, stride, pad), dt, "Y")
+        check(host(gX), oracle.conv_dgrad(dYo, Wo_, (Hh, Ww), stride, pad), dt, "dX")
+        check(host(gW), oracle.conv_wgrad(dYo, Xo, k, stride, pad), dt, "dW")
