@@ -1,0 +1,299 @@
+"""Benchmark: one training step (forward + backward) of a 12-block encoder FFN stack whose
+linears are SVD-decomposed, rank-quantized and sequentially frozen, on one MI355X.
+
+Workload (synthetic, seeded): 12 x {Linear 768->3072, GELU, Linear 3072->768}; every weight
+W ~ N(0, 1/fan_in) is decomposed by truncated SVD at rank 25% of min(in,out) = 192 (a multiple
+of 64); tokens = batch 32 x seq 256 = 8192, bf16 activations ~ N(0,1); the freeze mask of step s
+is Algorithm 2's mask for epoch s (V frozen on even steps, U frozen on odd steps).
+
+Prints ONE JSON line.  `value` is the algorithmic TFLOP/s of the decomposed layers (FLOPs as
+masked by freezing; GELU glue time is inside the step but adds no FLOPs to the numerator), with
+all inputs resident in HBM before the timed region.  Extra fields: tokens/s, the dense
+(undecomposed) stack and the unquantized-rank/unfrozen stack timed in the same run, the roofline
+of the dominant kernel, and the CPU oracle's rate on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+T_TOKENS, D_MODEL, D_FF, N_BLOCKS = 8192, 768, 3072, 12
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def layer_flops(T, n_in, n_out, r, mask, want_dx=True):
+    fwd = 2 * T * r * (n_in + n_out)
+    bwd = 2 * T * r * n_out + (2 * T * r * n_in if want_dx else 0)
+    bwd += 0 if mask & 2 else 2 * T * r * n_out
+    bwd += 0 if mask & 1 else 2 * T * r * n_in
+    return fwd, bwd
+
+
+class Stack:
+    """Buffers and factors of the 12-block stack; fwd/bwd through the library only."""
+
+    def __init__(self, lrd, torch, np, si, factorize, rank, seed_stream, true_svd=True):
+        self.lrd, self.torch = lrd, torch
+        dev = "cuda"
+        bf = torch.bfloat16
+        rng = si.rng_for(2, seed_stream)
+        self.r = rank
+        self.layers = []
+        T = T_TOKENS
+
+        def to_dev(a):
+            bits = si.bf16_bits(a).view(np.int16)
+            return torch.from_numpy(bits).to(dev).view(bf).reshape(a.shape)
+
+        for b in range(N_BLOCKS):
+            blk = []
+            for (n_in, n_out) in ((D_MODEL, D_FF), (D_FF, D_MODEL)):
+                if true_svd:
+                    W = si.linear_weight(n_out, n_in, rng)
+                    U, V, _ = factorize.svd_factors(W, rank)
+                else:
+                    U, V = si.direct_factors(n_out, n_in, rank, rng)
+                blk.append(dict(n_in=n_in, n_out=n_out, U=to_dev(U), V=to_dev(V),
+                                H=torch.empty((T, rank), dtype=bf, device=dev),
+                                dU=torch.empty((n_out, rank), dtype=torch.float32, device=dev),
+                                dV=torch.empty((rank, n_in), dtype=torch.float32, device=dev)))
+            self.layers.append(blk)
+        self.X = [to_dev(si.gaussian((T, D_MODEL), rng))]
+        self.X += [torch.empty((T, D_MODEL), dtype=bf, device=dev) for _ in range(N_BLOCKS)]
+        self.Z = [torch.empty((T, D_FF), dtype=bf, device=dev) for _ in range(N_BLOCKS)]
+        self.A = [torch.empty((T, D_FF), dtype=bf, device=dev) for _ in range(N_BLOCKS)]
+        self.gX = [torch.empty((T, D_MODEL), dtype=bf, device=dev) for _ in range(2)]
+        self.gA = torch.empty((T, D_FF), dtype=bf, device=dev)
+        self.gZ = torch.empty((T, D_FF), dtype=bf, device=dev)
+        nbytes = max(lrd.linear_workspace_bytes(T, D_MODEL, D_FF, rank, lrd.BF16, 0),
+                     lrd.linear_workspace_bytes(T, D_FF, D_MODEL, rank, lrd.BF16, 0))
+        self.ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+        self.probe = None     # optional (start_event, end_event) list filled around one call class
+
+    def forward(self):
+        lrd = self.lrd
+        for b, (l1, l2) in enumerate(self.layers):
+            if self.probe is not None:
+                s, e = self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
+                s.record()
+            lrd.linear_fwd(self.X[b], l1["V"], l1["U"], None, self.Z[b], l1["H"], self.ws)
+            if self.probe is not None:
+                e.record()
+                self.probe.append((s, e))
+            lrd.gelu_fwd(self.Z[b], self.A[b])
+            lrd.linear_fwd(self.A[b], l2["V"], l2["U"], None, self.X[b + 1], l2["H"], self.ws)
+
+    def backward(self, mask):
+        """Loss 0.5 ||Y||^2: the gradient entering the last block is the stack's output."""
+        lrd = self.lrd
+        g = self.X[N_BLOCKS]
+        for b in reversed(range(N_BLOCKS)):
+            l1, l2 = self.layers[b]
+            out = self.gX[b & 1]
+            lrd.linear_bwd(g, self.A[b], l2["H"], l2["V"], l2["U"], self.gA, l2["dV"], l2["dU"], None, mask, self.ws)
+            lrd.gelu_bwd(self.gA, self.Z[b], self.gZ)
+            lrd.linear_bwd(self.gZ, self.X[b], l1["H"], l1["V"], l1["U"], out if b > 0 else None,
+                           l1["dV"], l1["dU"], None, mask, self.ws)
+            g = out
+
+    def step(self, mask):
+        self.forward()
+        self.backward(mask)
+
+    def flops(self, mask):
+        tot = 0
+        for b in range(N_BLOCKS):
+            f1, b1 = layer_flops(T_TOKENS, D_MODEL, D_FF, self.r, mask, want_dx=b > 0)
+            f2, b2 = layer_flops(T_TOKENS, D_FF, D_MODEL, self.r, mask)
+            tot += f1 + b1 + f2 + b2
+        return tot
+
+
+class DenseStack:
+    def __init__(self, lrd, torch, np, si):
+        self.lrd = lrd
+        dev, bf = "cuda", torch.bfloat16
+        rng = si.rng_for(2, 7)
+        T = T_TOKENS
+
+        def to_dev(a):
+            bits = si.bf16_bits(a).view(np.int16)
+            return torch.from_numpy(bits).to(dev).view(bf).reshape(a.shape)
+
+        self.W = [(to_dev(si.linear_weight(D_FF, D_MODEL, rng)), to_dev(si.linear_weight(D_MODEL, D_FF, rng)))
+                  for _ in range(N_BLOCKS)]
+        self.dW = (torch.empty((D_FF, D_MODEL), dtype=torch.float32, device=dev),
+                   torch.empty((D_MODEL, D_FF), dtype=torch.float32, device=dev))
+        self.X = [to_dev(si.gaussian((T, D_MODEL), rng))] + [torch.empty((T, D_MODEL), dtype=bf, device=dev) for _ in range(N_BLOCKS)]
+        self.Z = [torch.empty((T, D_FF), dtype=bf, device=dev) for _ in range(N_BLOCKS)]
+        self.A = [torch.empty((T, D_FF), dtype=bf, device=dev) for _ in range(N_BLOCKS)]
+        self.gX = [torch.empty((T, D_MODEL), dtype=bf, device=dev) for _ in range(2)]
+        self.gA = torch.empty((T, D_FF), dtype=bf, device=dev)
+        self.gZ = torch.empty((T, D_FF), dtype=bf, device=dev)
+        nbytes = max(lrd.dense_linear_workspace_bytes(T, D_MODEL, D_FF, lrd.BF16),
+                     lrd.dense_linear_workspace_bytes(T, D_FF, D_MODEL, lrd.BF16))
+        self.ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+
+    def step(self, mask=0):
+        lrd = self.lrd
+        for b, (w1, w2) in enumerate(self.W):
+            lrd.dense_linear_fwd(self.X[b], w1, None, self.Z[b], self.ws)
+            lrd.gelu_fwd(self.Z[b], self.A[b])
+            lrd.dense_linear_fwd(self.A[b], w2, None, self.X[b + 1], self.ws)
+        g = self.X[N_BLOCKS]
+        for b in reversed(range(N_BLOCKS)):
+            w1, w2 = self.W[b]
+            out = self.gX[b & 1]
+            lrd.dense_linear_bwd(g, self.A[b], w2, self.gA, self.dW[1], self.ws)
+            lrd.gelu_bwd(self.gA, self.Z[b], self.gZ)
+            lrd.dense_linear_bwd(self.gZ, self.X[b], w1, out if b > 0 else None, self.dW[0], self.ws)
+            g = out
+
+
+def timed(torch, fn, steps, warmup, first_step=0):
+    for s in range(warmup):
+        fn(s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(first_step, first_step + steps):
+        fn(s)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def cpu_baseline(np, si, oracle, rank):
+    """The fp64 oracle, as it stands, on one full step of the workload (all blocks, all tokens)."""
+    rng = si.rng_for(2, 99)
+    T = T_TOKENS
+    blocks = N_BLOCKS
+    X = si.round_bf16(si.gaussian((T, D_MODEL), rng))
+    fac = []
+    for _ in range(blocks):
+        fac.append([tuple(si.round_bf16(a) for a in si.direct_factors(D_FF, D_MODEL, rank, rng)),
+                    tuple(si.round_bf16(a) for a in si.direct_factors(D_MODEL, D_FF, rank, rng))])
+    mask = oracle.freeze_mask(oracle.KIND_SVD, 0)
+    t0 = time.perf_counter()
+    saved = []
+    x = X
+    for (U1, V1), (U2, V2) in fac:
+        H1, Z = oracle.linear_fwd(x, V1, U1)
+        A = oracle.gelu_fwd(Z)
+        H2, y = oracle.linear_fwd(A, V2, U2)
+        saved.append((x, H1, Z, A, H2))
+        x = y
+    g = x
+    for ((U1, V1), (U2, V2)), (x0, H1, Z, A, H2) in zip(reversed(fac), reversed(saved)):
+        b2 = oracle.linear_bwd(g, A, H2, V2, U2, mask)
+        gz = oracle.gelu_bwd(b2["dX"], Z)
+        b1 = oracle.linear_bwd(gz, x0, H1, V1, U1, mask)
+        g = b1["dX"]
+    dt = time.perf_counter() - t0
+    flops = 0
+    for _ in range(blocks):
+        for (n_in, n_out) in ((D_MODEL, D_FF), (D_FF, D_MODEL)):
+            f, b = layer_flops(T, n_in, n_out, rank, mask)
+            flops += f + b
+    return dict(value=flops / dt / 1e12, unit="TFLOP/s", cores=oracle.threads(), kind="oracle",
+                sample=f"{blocks} of {N_BLOCKS} FFN blocks, all {T} tokens, fwd+bwd with V frozen, fp64; {dt:.1f} s",
+                tokens_per_s=T / (dt * N_BLOCKS / blocks))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-comparators", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import synth_inputs as si
+    from paper_2309_03824_amd import binding as lrd
+    from paper_2309_03824_amd import factorize
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+
+    rank = lrd.quantize_rank(int(0.25 * min(D_MODEL, D_FF)), 64)
+    stack = Stack(lrd, torch, np, si, factorize, rank, seed_stream=0, true_svd=True)
+
+    def one(s):
+        stack.step(lrd.freeze_mask(lrd.KIND_SVD, s))
+
+    for s in range(args.warmup):
+        one(s)
+    torch.cuda.synchronize()
+    stack.probe = []
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        one(s)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    probe, stack.probe = stack.probe, None
+
+    flops_even, flops_odd = stack.flops(1), stack.flops(2)
+    n_even = (args.steps + 1) // 2
+    flops = (flops_even * n_even + flops_odd * (args.steps - n_even)) / args.steps
+    tflops = flops / (ms * 1e-3) / 1e12
+
+    # Dominant kernel: the fused forward pair (one launch per lrd_linear_fwd call), 768 -> 3072 shape.
+    # Algorithmic bytes per launch: X read + Z written + H side-stored + both factors, bf16.
+    k_us = sum(s.elapsed_time(e) for s, e in probe) * 1e3 / len(probe)
+    k_bytes = 2 * (T_TOKENS * D_MODEL + T_TOKENS * D_FF + T_TOKENS * rank + rank * (D_MODEL + D_FF))
+    achieved = k_bytes / (k_us * 1e-6) / 1e9
+    roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved / HBM_PEAK_GBS,
+                    traffic=None, kernel="chain_kernel (lrd_linear_fwd 768->3072)", avg_us=k_us,
+                    bytes_per_launch=k_bytes)
+
+    out = dict(metric="decomposed-layer fwd+bwd throughput (12-block encoder FFN stack)", value=tflops,
+               unit="TFLOP/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms,
+               higher_is_better=True, scaling="weak", vs_baseline=None, dtype="bf16", data="synthetic",
+               config=dict(workload="encoder FFN stack: 12 x (768->3072, GELU, 3072->768), SVD rank 192 (25%, multiple of 64), "
+                                    "8192 tokens (32 x 256), sequential freezing alternating V/U per step",
+                           tokens=T_TOKENS, rank=rank, blocks=N_BLOCKS),
+               tokens_per_s=T_TOKENS / (ms * 1e-3), frac_bf16_mfma_peak=tflops / MFMA_BF16_PEAK_TFLOPS,
+               roofline=roofline)
+
+    if not args.no_comparators:
+        k = max(4, args.steps // 2)
+        dense = DenseStack(lrd, torch, np, si)
+        d_ms = timed(torch, lambda s: dense.step(), k, 2)
+        del dense
+        torch.cuda.empty_cache()
+        raw_rank = rank - 1            # an unquantized rank next to it, nothing frozen: "vanilla" decomposition
+        vanilla = Stack(lrd, torch, np, si, factorize, raw_rank, seed_stream=1, true_svd=False)
+        v_ms = timed(torch, lambda s: vanilla.step(0), k, 2)
+        del vanilla
+        unfrozen = Stack(lrd, torch, np, si, factorize, rank, seed_stream=1, true_svd=False)
+        u_ms = timed(torch, lambda s: unfrozen.step(0), k, 2)
+        del unfrozen
+        out["comparators"] = dict(dense_ms_per_step=d_ms, dense_tflops=12 * 6 * T_TOKENS * D_MODEL * D_FF * 2 / (d_ms * 1e-3) / 1e12,
+                                  speedup_vs_dense=d_ms / ms,
+                                  vanilla_rank=raw_rank, vanilla_unfrozen_ms_per_step=v_ms,
+                                  quantized_unfrozen_ms_per_step=u_ms,
+                                  speedup_rank_quantization=v_ms / u_ms, speedup_freezing=u_ms / ms,
+                                  speedup_combined=v_ms / ms)
+    if not args.no_cpu_baseline:
+        import oracle
+        out["cpu_baseline"] = cpu_baseline(np, si, oracle, rank)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

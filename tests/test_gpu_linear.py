@@ -196,7 +196,11 @@ def test_gelu(dt):
 
 
 def test_errors_reported_by_status():
-    X = empty((8, 8), "bf16")
-    with pytest.raises(lrd.LrdError) as e:
-        lrd.linear_fwd(X, X[:4], X[:, :4].contiguous(), None, X, None, None)     # needs a workspace for H
+    X = empty((8, 8), "f32", 1.0)
+    dV, dU = f32((4, 8)), f32((8, 4))
+    with pytest.raises(lrd.LrdError) as e:     # the backward needs workspace for dH; none is given
+        lrd.linear_bwd(X, X, None, X[:4], X[:, :4].contiguous(), X.clone(), dV, dU, None, 0, None)
     assert e.value.status == lrd.ERR_WORKSPACE
+    with pytest.raises(lrd.LrdError) as e:     # rank above min(in, out)
+        lrd.linear_fwd(X, empty((9, 8), "f32"), empty((8, 9), "f32"), None, X.clone(), None, None)
+    assert e.value.status == lrd.ERR_INVALID_ARG
