@@ -28,7 +28,7 @@
  *     dtype LRD_F32: everything is fp32.
  *   - The caller owns every buffer, including the workspace `ws` (size from the matching
  *     *_workspace_bytes query; may be NULL when that query returns 0).  The library keeps no
- *     device memory and no mutable global state.
+ *     device memory; its only process-wide state is the tuning switch of lrd_set_fusion.
  *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default stream).
  *     No call synchronises or allocates.
  *   - Arguments are validated on the host before anything is launched; on a non-OK status
@@ -199,6 +199,17 @@ lrd_status lrd_dense_conv_fwd(const void* X, const void* W, void* Y, const lrd_c
 lrd_status lrd_dense_conv_bwd(const void* dY, const void* X, const void* W, void* dX, float* dW,
                               const lrd_conv_geom* g, lrd_dtype dt, void* ws, size_t ws_bytes,
                               void* hip_stream);
+
+/*
+ * Tuning switch for callers that measure: how a bf16 pair with r <= 256 is evaluated.
+ * LRD_FUSION_AUTO (default) lets the library choose per shape; LRD_FUSION_ALWAYS keeps the rank-r
+ * intermediate in LDS between the two products whenever the fused kernel supports the shape;
+ * LRD_FUSION_NEVER runs two separate products through an intermediate in memory (H_save or the
+ * workspace).  Results agree up to fp32 summation order.  Process-wide; returns the previous mode,
+ * or -1 (and changes nothing) for an unknown mode.
+ */
+enum { LRD_FUSION_AUTO = 0, LRD_FUSION_ALWAYS = 1, LRD_FUSION_NEVER = 2 };
+int32_t lrd_set_fusion(int32_t mode);
 
 /* ------------------------------------------------------------------------------------------
  * Glue between stacked layers (not part of the method; used by the layer-stack workloads)

@@ -19,6 +19,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_ALIGNMENT, ERR_WORKSPACE, ERR_RUNTIME 
 F32, BF16 = 0, 1
 KIND_SVD, KIND_TUCKER = 0, 1
 FREEZE_L0, FREEZE_L1, FREEZE_L2 = 1, 2, 4
+FUSION_AUTO, FUSION_ALWAYS, FUSION_NEVER = 0, 1, 2
 ROUND_NEAREST, ROUND_DOWN, ROUND_UP = 0, 1, 2
 
 EXPORTS = (
@@ -27,7 +28,7 @@ EXPORTS = (
     "lrd_dense_linear_workspace_bytes", "lrd_dense_linear_fwd", "lrd_dense_linear_bwd",
     "lrd_tucker_conv_workspace_bytes", "lrd_tucker_conv_fwd", "lrd_tucker_conv_bwd",
     "lrd_dense_conv_workspace_bytes", "lrd_dense_conv_fwd", "lrd_dense_conv_bwd",
-    "lrd_gelu_fwd", "lrd_gelu_bwd",
+    "lrd_gelu_fwd", "lrd_gelu_bwd", "lrd_set_fusion",
 )
 
 
@@ -89,6 +90,8 @@ def _load() -> ctypes.CDLL:
     lib.lrd_dense_conv_bwd.argtypes = [P] * 5 + [G, ctypes.c_int, P, SZ, P]
     lib.lrd_gelu_fwd.restype = ctypes.c_int
     lib.lrd_gelu_fwd.argtypes = [P, P, I64, ctypes.c_int, P]
+    lib.lrd_set_fusion.restype = c_int32
+    lib.lrd_set_fusion.argtypes = [c_int32]
     lib.lrd_gelu_bwd.restype = ctypes.c_int
     lib.lrd_gelu_bwd.argtypes = [P, P, P, I64, ctypes.c_int, P]
     return lib
@@ -159,6 +162,13 @@ def svd_rank(n_in: int, n_out: int, alpha: float) -> int:
     if r < 0:
         raise LrdError(-r, "lrd_svd_rank")
     return int(r)
+
+
+def set_fusion(mode: int) -> int:
+    prev = int(_lib.lrd_set_fusion(mode))
+    if prev < 0:
+        raise LrdError(ERR_INVALID_ARG, "lrd_set_fusion")
+    return prev
 
 
 # ------------------------------------------------------------------------------- linear pair

@@ -19,6 +19,7 @@ int choose_splits(int64_t M, int64_t N, int64_t K, bool in_bf16)
 
 hipError_t run_matop(const MatOp& op, hipStream_t st)
 {
+    if (mfma_gemm2_supported(op)) return mfma_gemm2(op, st);
     if (mfma_matop_supported(op)) return mfma_matop(op, st);
     return generic_matop(op, st);
 }

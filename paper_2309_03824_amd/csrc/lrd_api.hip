@@ -1,12 +1,26 @@
 // C-ABI entry points: argument validation, workspace carving, and the composition of each layer
 // pass out of matrix products (see lrd.h for the contract of every call).
 #include <algorithm>
+#include <atomic>
 
 #include "lrd.h"
 #include "lrd_internal.hpp"
 
 namespace lrd {
 namespace {
+
+std::atomic<int> g_fusion{LRD_FUSION_AUTO};
+
+// Whether the fused pair kernel should take this shape.  AUTO: measured on MI355X, two separate
+// products are faster at every workload shape tried so far (the fused kernel runs one workgroup
+// per compute unit and pays a barrier per K-step), so AUTO currently resolves to "no".
+inline bool want_fusion(const ChainOp& ch)
+{
+    int mode = g_fusion.load(std::memory_order_relaxed);
+    if (mode == LRD_FUSION_NEVER) return false;
+    if (!mfma_chain_supported(ch)) return false;
+    return mode == LRD_FUSION_ALWAYS;
+}
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round256(size_t b) { return (b + 255) & ~size_t(255); }
@@ -120,6 +134,12 @@ using namespace lrd;
 
 extern "C" {
 
+int32_t lrd_set_fusion(int32_t mode)
+{
+    if (mode != LRD_FUSION_AUTO && mode != LRD_FUSION_ALWAYS && mode != LRD_FUSION_NEVER) return -1;
+    return g_fusion.exchange(mode);
+}
+
 // ------------------------------------------------------------------------------------ linear
 size_t lrd_linear_workspace_bytes(int64_t T, int64_t in, int64_t out, int64_t r, lrd_dtype dt,
                                   uint32_t freeze_mask)
@@ -151,7 +171,7 @@ lrd_status lrd_linear_fwd(const void* X, const void* V, const void* U, const flo
         ch.mid_save = H_save; ch.ldmid = r;
         ch.bias = bias;
         ch.M = T; ch.K1 = in; ch.R = r; ch.N2 = out;
-        if (mfma_chain_supported(ch)) {
+        if (want_fusion(ch)) {
             LRD_TRY(mfma_chain(ch, st));
             return LRD_OK;
         }
@@ -217,7 +237,7 @@ lrd_status lrd_linear_bwd(const void* dY, const void* X, const void* H, const vo
             ch.C = dX; ch.ldc = in;
             ch.mid_save = train_v ? dH : nullptr; ch.ldmid = r;
             ch.M = T; ch.K1 = out; ch.R = r; ch.N2 = in;
-            if (mfma_chain_supported(ch)) {
+            if (want_fusion(ch)) {
                 LRD_TRY(mfma_chain(ch, st));
                 fused = true;
             }

@@ -41,6 +41,8 @@ struct MatOp {
 hipError_t generic_matop(const MatOp& op, hipStream_t st);          // any MatOp, plain FMA tiles
 bool mfma_matop_supported(const MatOp& op);                         // bf16 MFMA engine covers it?
 hipError_t mfma_matop(const MatOp& op, hipStream_t st);
+bool mfma_gemm2_supported(const MatOp& op);                        // aligned fast path covers it?
+hipError_t mfma_gemm2(const MatOp& op, hipStream_t st);
 hipError_t run_matop(const MatOp& op, hipStream_t st);              // picks an engine
 
 // Workspace floats a MatOp of this shape needs for split-K (0 if it will not be split).

@@ -1,0 +1,358 @@
+// bf16 MFMA product kernel for 16-byte-aligned operands (the common case: every leading dimension
+// a multiple of 8 elements).  One kernel template covers the three operand layouts of a layer:
+//   forward / unfused pair      C = A . B^T          A [M x K], B [N x K]   (both k-contiguous)
+//   data gradient               C = A . B            A [M x K], B [K x N]   (B k-major)
+//   weight gradient (fp32 out)  C = A^T . B          A [K x M], B [K x N]   (both k-major), split-K
+//
+// Main loop: straight-line code, no data-dependent branches.  Every thread owns fixed 16-byte
+// chunks of the operand tiles; out-of-range rows / k are handled by clamping the ADDRESS (so the
+// load is always legal) and zeroing the VALUE when it is written to LDS, which keeps the loads
+// free of consumers and lets them stay in flight across DEPTH K-steps.  K-major operands are read
+// as 8 k x 8 column units and transposed in registers on their way into LDS.  bf16 results leave
+// through LDS so that each lane stores 16 contiguous bytes of an output row.
+#include "lrd_internal.hpp"
+
+namespace lrd {
+namespace {
+
+constexpr int BK = 64;
+constexpr int LDK = BK + 8;
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+struct Operand {
+    const bf16_t* p;
+    int64_t ld;   // elements between rows of the stored matrix
+    int rows;     // extent along the tile's row index (M for A, N for B)
+};
+
+// ---- k-contiguous tile: ROWS x BK, chunk c -> row c>>3, k-chunk c&7 ------------------------------
+template <int ROWS, int NT, int DEPTH>
+struct KcTile {
+    static constexpr int CH = (ROWS * 8 + NT - 1) / NT;
+    static constexpr bool FULL = (ROWS * 8) % NT == 0;
+    const bf16_t* ptr[CH];
+    bool rowok[CH];
+    int kc8[CH];
+    u32x4 st[DEPTH][CH];
+
+    __device__ __forceinline__ void init(const Operand& o, int row0, int tid)
+    {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            int c = tid + i * NT;
+            int row = row0 + (c >> 3);
+            rowok[i] = row < o.rows;
+            kc8[i] = (c & 7) * 8;
+            ptr[i] = o.p + (int64_t)min(row, o.rows - 1) * o.ld;
+        }
+    }
+    __device__ __forceinline__ void load(int d, int k0, int kend, int tid)
+    {
+#pragma unroll
+        for (int i = 0; i < CH; ++i)
+            if (FULL || tid + i * NT < ROWS * 8)
+                st[d][i] = *reinterpret_cast<const u32x4*>(ptr[i] + min(k0 + kc8[i], kend - 8));
+    }
+    __device__ __forceinline__ void store(int d, bf16_t* lds, int k0, int kend, int tid) const
+    {
+        const u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            int c = tid + i * NT;
+            if (FULL || c < ROWS * 8)
+                *reinterpret_cast<u32x4*>(lds + (c >> 3) * LDK + (c & 7) * 8) =
+                    (rowok[i] && k0 + kc8[i] < kend) ? st[d][i] : z;
+        }
+    }
+};
+
+// ---- k-major tile: BK x COLS read as 8 k x 8 column units, unit u -> k-block u&7, column block u>>3
+template <int COLS, int NT, int DEPTH>
+struct KmTile {
+    static constexpr int UN = (COLS + NT - 1) / NT;
+    static constexpr bool FULL = COLS % NT == 0;
+    const bf16_t* ptr[UN];
+    bool colok[UN];
+    int kb8[UN];
+    int64_t ld;
+    u32x4 st[DEPTH][UN][8];
+
+    __device__ __forceinline__ void init(const Operand& o, int col0, int tid)
+    {
+        ld = o.ld;
+#pragma unroll
+        for (int i = 0; i < UN; ++i) {
+            int u = tid + i * NT;
+            int col = col0 + (u >> 3) * 8;
+            colok[i] = col < o.rows;
+            kb8[i] = (u & 7) * 8;
+            ptr[i] = o.p + min(col, o.rows - 8);
+        }
+    }
+    __device__ __forceinline__ void load(int d, int k0, int kend, int tid)
+    {
+#pragma unroll
+        for (int i = 0; i < UN; ++i)
+            if (FULL || tid + i * NT < COLS) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    st[d][i][e] = *reinterpret_cast<const u32x4*>(ptr[i] + (int64_t)min(k0 + kb8[i] + e, kend - 1) * ld);
+            }
+    }
+    __device__ __forceinline__ void store(int d, bf16_t* lds, int k0, int kend, int tid) const
+    {
+        const u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < UN; ++i) {
+            int u = tid + i * NT;
+            if (FULL || u < COLS) {
+                const bool ok = colok[i] && k0 + kb8[i] < kend;   // kend is a multiple of 8
+#pragma unroll
+                for (int n = 0; n < 8; ++n) {
+                    u32x4 o;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        uint32_t a = st[d][i][2 * q][n >> 1], b = st[d][i][2 * q + 1][n >> 1];
+                        o[q] = (n & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
+                    }
+                    *reinterpret_cast<u32x4*>(lds + ((u >> 3) * 8 + n) * LDK + (u & 7) * 8) = ok ? o : z;
+                }
+            }
+        }
+    }
+};
+
+template <int ROWS, int NT, int DEPTH, bool KM>
+struct Tile;
+template <int ROWS, int NT, int DEPTH>
+struct Tile<ROWS, NT, DEPTH, false> : KcTile<ROWS, NT, DEPTH> {};
+template <int ROWS, int NT, int DEPTH>
+struct Tile<ROWS, NT, DEPTH, true> : KmTile<ROWS, NT, DEPTH> {};
+
+template <int TM, int TN>
+__device__ __forceinline__ void mma_step(f32x16 (&acc)[TM][TN], const bf16_t* a_lds, const bf16_t* b_lds, int lane)
+{
+    const int r = lane & 31, kh = (lane >> 5) * 8;
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+        bf16x8 a[TM], b[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const bf16x8*>(a_lds + (i * 32 + r) * LDK + kk * 16 + kh);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const bf16x8*>(b_lds + (j * 32 + r) * LDK + kk * 16 + kh);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(b[j], a[i], acc[i][j]);   // roles swapped: lane <-> row m
+    }
+}
+
+template <int BM, int BN, class OutT>
+constexpr int gemm2_lds_bytes()
+{
+    int main = 2 * (BM + BN) * LDK * 2;
+    int epi = sizeof(OutT) == 2 ? BM * (BN + 8) * 2 : 0;
+    return main > epi ? main : epi;
+}
+
+template <int BM, int BN, int WGM, int WGN, int DEPTH, bool A_KM, bool B_KM, class OutT>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm2_kernel(Operand A, Operand B, OutT* __restrict__ C, int64_t ldc,
+                                                               const float* __restrict__ bias, float* __restrict__ partial,
+                                                               int M, int N, int K, int k_per_split)
+{
+    constexpr int NT = 64 * WGM * WGN;
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int STAGE = (BM + BN) * LDK;
+    extern __shared__ __align__(16) unsigned char smem[];
+    bf16_t* lds = reinterpret_cast<bf16_t*>(smem);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    const int kbeg = blockIdx.z * k_per_split;
+    const int kend = min(K, kbeg + k_per_split);
+    const int nk = (kend - kbeg + BK - 1) / BK;
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    Tile<BM, NT, DEPTH, A_KM> ta;
+    Tile<BN, NT, DEPTH, B_KM> tb;
+    ta.init(A, m0, tid);
+    tb.init(B, n0, tid);
+
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d)
+        if (d < nk) {
+            ta.load(d, kbeg + d * BK, kend, tid);
+            tb.load(d, kbeg + d * BK, kend, tid);
+        }
+    if (nk > 0) {
+        ta.store(0, lds, kbeg, kend, tid);
+        tb.store(0, lds + BM * LDK, kbeg, kend, tid);
+    }
+    __syncthreads();
+    for (int kt0 = 0; kt0 < nk; kt0 += DEPTH) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            const int kt = kt0 + d;
+            if (kt < nk) {
+                bf16_t* cur = lds + (kt & 1) * STAGE;
+                bf16_t* nxt = lds + ((kt + 1) & 1) * STAGE;
+                if (kt + DEPTH < nk) {
+                    ta.load(d, kbeg + (kt + DEPTH) * BK, kend, tid);
+                    tb.load(d, kbeg + (kt + DEPTH) * BK, kend, tid);
+                }
+                mma_step<TM, TN>(acc, cur + wm * WTM * LDK, cur + BM * LDK + wn * WTN * LDK, lane);
+                if (kt + 1 < nk) {
+                    ta.store((d + 1) % DEPTH, nxt, kbeg + (kt + 1) * BK, kend, tid);
+                    tb.store((d + 1) % DEPTH, nxt + BM * LDK, kbeg + (kt + 1) * BK, kend, tid);
+                }
+                __syncthreads();
+            }
+        }
+    }
+
+    const int r = lane & 31, h = lane >> 5;
+    if constexpr (sizeof(OutT) == 4) {
+        // fp32 results (weight gradients or their split-K partials): 16-byte stores straight from registers
+        float* out = partial ? partial + (int64_t)blockIdx.z * M * N : reinterpret_cast<float*>(C);
+        const int64_t ldo = partial ? (int64_t)N : ldc;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            int m = m0 + wm * WTM + i * 32 + r;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    int n = n0 + wn * WTN + j * 32 + 8 * g + 4 * h;
+                    if (m < M && n < N) {   // N is a multiple of 4 on this path
+                        f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                        *reinterpret_cast<f32x4*>(out + (int64_t)m * ldo + n) = v;
+                    }
+                }
+        }
+    } else {
+        // bf16 results: registers -> LDS tile (row-major) -> 16 contiguous bytes per lane to global memory
+        constexpr int LDC = BN + 8;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            int ml = wm * WTM + i * 32 + r;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    int nl = wn * WTN + j * 32 + 8 * g + 4 * h;
+                    f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                    if (bias) {
+                        int n = min(n0 + nl, N - 4);
+                        f32x4 b4 = *reinterpret_cast<const f32x4*>(bias + n);
+                        v += b4;
+                    }
+                    u32x2 pk = {pack_bf16(v.x, v.y), pack_bf16(v.z, v.w)};
+                    *reinterpret_cast<u32x2*>(lds + ml * LDC + nl) = pk;
+                }
+        }
+        __syncthreads();
+        constexpr int CPR = BN / 8;
+        bf16_t* out = reinterpret_cast<bf16_t*>(C);
+#pragma unroll 4
+        for (int c = tid; c < BM * CPR; c += NT) {
+            int ml = c / CPR, cc = c % CPR;
+            int m = m0 + ml, n = n0 + cc * 8;
+            if (m < M && n < N) {   // N is a multiple of 8 on this path
+                u32x4 v = *reinterpret_cast<const u32x4*>(lds + ml * LDC + cc * 8);
+                *reinterpret_cast<u32x4*>(out + (int64_t)m * ldc + n) = v;
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WGM, int WGN, int DEPTH, bool A_KM, bool B_KM, class OutT>
+hipError_t launch(const MatOp& op, const Operand& A, const Operand& B, hipStream_t st)
+{
+    constexpr int NT = 64 * WGM * WGN;
+    constexpr int lds_bytes = gemm2_lds_bytes<BM, BN, OutT>();
+    auto kern = gemm2_kernel<BM, BN, WGM, WGN, DEPTH, A_KM, B_KM, OutT>;
+    static bool lds_allowed = false;
+    if (!lds_allowed) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           lds_bytes);
+        if (e != hipSuccess) return e;
+        lds_allowed = true;
+    }
+    int splits = (op.splits > 1 && op.partial) ? op.splits : 1;
+    int kps = (int)(ceil_div(ceil_div(op.K, splits), BK) * BK);
+    splits = (int)ceil_div(op.K, kps);
+    float* partial = splits > 1 ? op.partial : nullptr;
+    dim3 grid((unsigned)ceil_div(op.M, BM), (unsigned)ceil_div(op.N, BN), (unsigned)splits);
+    hipLaunchKernelGGL(kern, grid, dim3(NT), lds_bytes, st, A, B, (OutT*)op.C, op.ldc, op.bias, partial, (int)op.M,
+                       (int)op.N, (int)op.K, kps);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (splits > 1) return reduce_partials(op.partial, (float*)op.C, op.ldc, op.M, op.N, splits, st);
+    return hipSuccess;
+}
+
+inline bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Tile choice: the largest tile that still yields about one workgroup per compute unit.
+template <bool A_KM, bool B_KM, class OutT>
+hipError_t by_tile(const MatOp& op, const Operand& A, const Operand& B, hipStream_t st)
+{
+    const int64_t splits = (op.splits > 1 && op.partial) ? op.splits : 1;
+    auto wgs = [&](int bm, int bn) { return ceil_div(op.M, bm) * ceil_div(op.N, bn) * splits; };
+    if constexpr (sizeof(OutT) == 2 && !A_KM && !B_KM) {
+        if (op.K >= 1024 && wgs(256, 256) >= 224) return launch<256, 256, 2, 4, 2, false, false, OutT>(op, A, B, st);
+    }
+    if (wgs(128, 128) >= 200 || (op.M > 64 && op.N > 64 && wgs(64, 64) > 2048))
+        return launch<128, 128, 2, 2, (A_KM || B_KM) ? 1 : 2, A_KM, B_KM, OutT>(op, A, B, st);
+    return launch<64, 64, 2, 2, 2, A_KM, B_KM, OutT>(op, A, B, st);
+}
+
+}  // namespace
+
+bool mfma_gemm2_supported(const MatOp& op)
+{
+    if (!op.in_bf16 || op.gather != GATHER_NONE) return false;
+    if (op.M < 1 || op.N < 1 || op.K < 8) return false;
+    if (op.M >= (int64_t(1) << 31) || op.N >= (int64_t(1) << 31) || op.K >= (int64_t(1) << 31)) return false;
+    if (!al16(op.A) || !al16(op.B) || !al16(op.C) || op.K % 8 != 0) return false;
+    const bool akm = op.a_sk != 1, bkm = op.b_sk != 1;
+    if (akm && (op.a_sm != 1 || op.a_sk % 8 != 0 || op.M % 8 != 0)) return false;
+    if (!akm && op.a_sm % 8 != 0) return false;
+    if (bkm && (op.b_sn != 1 || op.b_sk % 8 != 0 || op.N % 8 != 0)) return false;
+    if (!bkm && op.b_sn % 8 != 0) return false;
+    if (akm && !bkm) return false;                       // layout not used by any layer pass
+    if (op.out_f32) {
+        if (!(akm && bkm)) return false;                 // fp32 results are weight gradients
+        if (op.N % 4 != 0 || op.ldc % 4 != 0 || op.bias) return false;
+    } else {
+        if (akm) return false;
+        if (op.N % 8 != 0 || op.ldc % 8 != 0 || op.splits > 1) return false;
+        if (op.bias && (op.N < 4 || (reinterpret_cast<uintptr_t>(op.bias) & 15u))) return false;
+    }
+    if (ceil_div(op.N, 64) > 65535) return false;
+    return true;
+}
+
+hipError_t mfma_gemm2(const MatOp& op, hipStream_t st)
+{
+    const bool akm = op.a_sk != 1, bkm = op.b_sk != 1;
+    Operand A{(const bf16_t*)op.A, akm ? op.a_sk : op.a_sm, (int)op.M};
+    Operand B{(const bf16_t*)op.B, bkm ? op.b_sk : op.b_sn, (int)op.N};
+    if (op.out_f32) return by_tile<true, true, float>(op, A, B, st);
+    if (bkm) return by_tile<false, true, bf16_t>(op, A, B, st);
+    return by_tile<false, false, bf16_t>(op, A, B, st);
+}
+
+}  // namespace lrd

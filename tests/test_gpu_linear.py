@@ -11,6 +11,17 @@ from paper_2309_03824_amd import binding as lrd
 
 pytestmark = pytest.mark.gpu
 
+
+@pytest.fixture(params=["auto", "fused", "unfused"], autouse=True)
+def fusion_mode(request):
+    """Every test of this module runs with the library's default choice, with the rank-r
+    intermediate kept in LDS wherever the fused kernel supports the shape, and with two
+    separate products."""
+    mode = {"auto": lrd.FUSION_AUTO, "fused": lrd.FUSION_ALWAYS, "unfused": lrd.FUSION_NEVER}[request.param]
+    prev = lrd.set_fusion(mode)
+    yield request.param
+    lrd.set_fusion(prev)
+
 SENT = -1234.5
 
 
