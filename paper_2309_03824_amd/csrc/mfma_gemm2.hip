@@ -7,9 +7,10 @@
 // Main loop: straight-line code, no data-dependent branches.  Every thread owns fixed 16-byte
 // chunks of the operand tiles; out-of-range rows / k are handled by clamping the ADDRESS (so the
 // load is always legal) and zeroing the VALUE when it is written to LDS, which keeps the loads
-// free of consumers and lets them stay in flight across DEPTH K-steps.  K-major operands are read
-// as 8 k x 8 column units and transposed in registers on their way into LDS.  bf16 results leave
-// through LDS so that each lane stores 16 contiguous bytes of an output row.
+// free of consumers and lets them stay in flight across DEPTH K-steps.  K-major operands are
+// copied to LDS as they lie in memory and transposed by the LDS read (ds_read_b64_tr_b16) when the
+// MFMA fragments are fetched, so no layout costs a VALU instruction.  bf16 results leave through
+// LDS so that each lane stores 16 contiguous bytes of an output row.
 #include "lrd_internal.hpp"
 
 namespace lrd {
@@ -70,58 +71,49 @@ struct KcTile {
     }
 };
 
-// ---- k-major tile: BK x COLS read as 8 k x 8 column units, unit u -> k-block u&7, column block u>>3
+// ---- k-major tile: BK x COLS kept in LDS as it is stored in memory ([k][column], columns
+// contiguous); chunk c -> k = c / (COLS/8), column chunk c % (COLS/8).  The transposition the MFMA
+// operand layout needs is done by the LDS read itself (ds_read_b64_tr_b16, see km_frag).
 template <int COLS, int NT, int DEPTH>
 struct KmTile {
-    static constexpr int UN = (COLS + NT - 1) / NT;
-    static constexpr bool FULL = COLS % NT == 0;
-    const bf16_t* ptr[UN];
-    bool colok[UN];
-    int kb8[UN];
+    static constexpr int CPK = COLS / 8;                 // 16-byte chunks per k row
+    static constexpr int LDM = COLS + 16;                // LDS row length: stride = 8 banks mod 32
+    static constexpr int CH = (BK * CPK + NT - 1) / NT;
+    static constexpr bool FULL = (BK * CPK) % NT == 0;
+    const bf16_t* ptr[CH];
+    bool colok[CH];
+    int krow[CH];
     int64_t ld;
-    u32x4 st[DEPTH][UN][8];
+    u32x4 st[DEPTH][CH];
 
     __device__ __forceinline__ void init(const Operand& o, int col0, int tid)
     {
         ld = o.ld;
 #pragma unroll
-        for (int i = 0; i < UN; ++i) {
-            int u = tid + i * NT;
-            int col = col0 + (u >> 3) * 8;
+        for (int i = 0; i < CH; ++i) {
+            int c = tid + i * NT;
+            int col = col0 + (c % CPK) * 8;
             colok[i] = col < o.rows;
-            kb8[i] = (u & 7) * 8;
+            krow[i] = c / CPK;
             ptr[i] = o.p + min(col, o.rows - 8);
         }
     }
     __device__ __forceinline__ void load(int d, int k0, int kend, int tid)
     {
 #pragma unroll
-        for (int i = 0; i < UN; ++i)
-            if (FULL || tid + i * NT < COLS) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    st[d][i][e] = *reinterpret_cast<const u32x4*>(ptr[i] + (int64_t)min(k0 + kb8[i] + e, kend - 1) * ld);
-            }
+        for (int i = 0; i < CH; ++i)
+            if (FULL || tid + i * NT < BK * CPK)
+                st[d][i] = *reinterpret_cast<const u32x4*>(ptr[i] + (int64_t)min(k0 + krow[i], kend - 1) * ld);
     }
     __device__ __forceinline__ void store(int d, bf16_t* lds, int k0, int kend, int tid) const
     {
         const u32x4 z = {0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int i = 0; i < UN; ++i) {
-            int u = tid + i * NT;
-            if (FULL || u < COLS) {
-                const bool ok = colok[i] && k0 + kb8[i] < kend;   // kend is a multiple of 8
-#pragma unroll
-                for (int n = 0; n < 8; ++n) {
-                    u32x4 o;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        uint32_t a = st[d][i][2 * q][n >> 1], b = st[d][i][2 * q + 1][n >> 1];
-                        o[q] = (n & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
-                    }
-                    *reinterpret_cast<u32x4*>(lds + ((u >> 3) * 8 + n) * LDK + (u & 7) * 8) = ok ? o : z;
-                }
-            }
+        for (int i = 0; i < CH; ++i) {
+            int c = tid + i * NT;
+            if (FULL || c < BK * CPK)
+                *reinterpret_cast<u32x4*>(lds + (c / CPK) * LDM + (c % CPK) * 8) =
+                    (colok[i] && k0 + krow[i] < kend) ? st[d][i] : z;
         }
     }
 };
@@ -133,17 +125,44 @@ struct Tile<ROWS, NT, DEPTH, false> : KcTile<ROWS, NT, DEPTH> {};
 template <int ROWS, int NT, int DEPTH>
 struct Tile<ROWS, NT, DEPTH, true> : KmTile<ROWS, NT, DEPTH> {};
 
-template <int TM, int TN>
-__device__ __forceinline__ void mma_step(f32x16 (&acc)[TM][TN], const bf16_t* a_lds, const bf16_t* b_lds, int lane)
+// Operand fragment of one 32-row block for one 16-wide k step, in the register layout of
+// v_mfma_f32_32x32x16_bf16: lane L holds row (L & 31), k = 8 * (L >> 5) + 0..7.
+// k-contiguous tile [row][k]: one 16-byte read.
+__device__ __forceinline__ bf16x8 kc_frag(const bf16_t* tile, int row_block, int kk, int lane)
 {
-    const int r = lane & 31, kh = (lane >> 5) * 8;
+    return *reinterpret_cast<const bf16x8*>(tile + (row_block * 32 + (lane & 31)) * LDK + kk * 16 + (lane >> 5) * 8);
+}
+
+// k-major tile [k][row]: two transposing reads.  Within a block of 16 lanes, ds_read_b64_tr_b16
+// hands lane l the element (l & 3) of the 8-byte words addressed by lanes (l >> 2) + 4e, e = 0..3.
+// Pointing lane s at [k = kb + (s >> 2)][row = rb + 4 * (s & 3)] therefore gives lane l the four
+// values k = kb..kb+3 of row rb + l.
+template <int LDM>
+__device__ __forceinline__ bf16x8 km_frag(const bf16_t* tile, int row_block, int kk, int lane)
+{
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    const int blk = lane >> 4, s = lane & 15;
+    const int rb = row_block * 32 + 16 * (blk & 1) + 4 * (s & 3);
+    const int kb = kk * 16 + 8 * (blk >> 1) + (s >> 2);
+    const bf16_t* p = tile + kb * LDM + rb;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p + 4 * LDM));
+    s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+template <int TM, int TN, bool A_KM, bool B_KM, int LDMA, int LDMB>
+__device__ __forceinline__ void mma_step(f32x16 (&acc)[TM][TN], const bf16_t* a_lds, int a_row0, const bf16_t* b_lds,
+                                         int b_row0, int lane)
+{
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
         bf16x8 a[TM], b[TN];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const bf16x8*>(a_lds + (i * 32 + r) * LDK + kk * 16 + kh);
+        for (int i = 0; i < TM; ++i) a[i] = A_KM ? km_frag<LDMA>(a_lds + a_row0, i, kk, lane) : kc_frag(a_lds + a_row0 * LDK, i, kk, lane);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const bf16x8*>(b_lds + (j * 32 + r) * LDK + kk * 16 + kh);
+        for (int j = 0; j < TN; ++j) b[j] = B_KM ? km_frag<LDMB>(b_lds + b_row0, j, kk, lane) : kc_frag(b_lds + b_row0 * LDK, j, kk, lane);
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -151,10 +170,14 @@ __device__ __forceinline__ void mma_step(f32x16 (&acc)[TM][TN], const bf16_t* a_
     }
 }
 
-template <int BM, int BN, class OutT>
+// Elements one operand tile occupies in LDS.
+template <int ROWS, bool KM>
+constexpr int tile_elems() { return KM ? BK * (ROWS + 16) : ROWS * LDK; }
+
+template <int BM, int BN, bool A_KM, bool B_KM, class OutT>
 constexpr int gemm2_lds_bytes()
 {
-    int main = 2 * (BM + BN) * LDK * 2;
+    int main = 2 * (tile_elems<BM, A_KM>() + tile_elems<BN, B_KM>()) * 2;
     int epi = sizeof(OutT) == 2 ? BM * (BN + 8) * 2 : 0;
     return main > epi ? main : epi;
 }
@@ -167,7 +190,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm2_kernel(Operand A, Operan
     constexpr int NT = 64 * WGM * WGN;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
-    constexpr int STAGE = (BM + BN) * LDK;
+    constexpr int A_ELEMS = tile_elems<BM, A_KM>();
+    constexpr int STAGE = A_ELEMS + tile_elems<BN, B_KM>();
     extern __shared__ __align__(16) unsigned char smem[];
     bf16_t* lds = reinterpret_cast<bf16_t*>(smem);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -198,7 +222,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm2_kernel(Operand A, Operan
         }
     if (nk > 0) {
         ta.store(0, lds, kbeg, kend, tid);
-        tb.store(0, lds + BM * LDK, kbeg, kend, tid);
+        tb.store(0, lds + A_ELEMS, kbeg, kend, tid);
     }
     __syncthreads();
     for (int kt0 = 0; kt0 < nk; kt0 += DEPTH) {
@@ -212,10 +236,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm2_kernel(Operand A, Operan
                     ta.load(d, kbeg + (kt + DEPTH) * BK, kend, tid);
                     tb.load(d, kbeg + (kt + DEPTH) * BK, kend, tid);
                 }
-                mma_step<TM, TN>(acc, cur + wm * WTM * LDK, cur + BM * LDK + wn * WTN * LDK, lane);
+                mma_step<TM, TN, A_KM, B_KM, BM + 16, BN + 16>(acc, cur, wm * WTM, cur + A_ELEMS, wn * WTN, lane);
                 if (kt + 1 < nk) {
                     ta.store((d + 1) % DEPTH, nxt, kbeg + (kt + 1) * BK, kend, tid);
-                    tb.store((d + 1) % DEPTH, nxt + BM * LDK, kbeg + (kt + 1) * BK, kend, tid);
+                    tb.store((d + 1) % DEPTH, nxt + A_ELEMS, kbeg + (kt + 1) * BK, kend, tid);
                 }
                 __syncthreads();
             }
@@ -281,7 +305,7 @@ template <int BM, int BN, int WGM, int WGN, int DEPTH, bool A_KM, bool B_KM, cla
 hipError_t launch(const MatOp& op, const Operand& A, const Operand& B, hipStream_t st)
 {
     constexpr int NT = 64 * WGM * WGN;
-    constexpr int lds_bytes = gemm2_lds_bytes<BM, BN, OutT>();
+    constexpr int lds_bytes = gemm2_lds_bytes<BM, BN, A_KM, B_KM, OutT>();
     auto kern = gemm2_kernel<BM, BN, WGM, WGN, DEPTH, A_KM, B_KM, OutT>;
     static bool lds_allowed = false;
     if (!lds_allowed) {
@@ -315,7 +339,7 @@ hipError_t by_tile(const MatOp& op, const Operand& A, const Operand& B, hipStrea
         if (op.K >= 1024 && wgs(256, 256) >= 224) return launch<256, 256, 2, 4, 2, false, false, OutT>(op, A, B, st);
     }
     if (wgs(128, 128) >= 200 || (op.M > 64 && op.N > 64 && wgs(64, 64) > 2048))
-        return launch<128, 128, 2, 2, (A_KM || B_KM) ? 1 : 2, A_KM, B_KM, OutT>(op, A, B, st);
+        return launch<128, 128, 2, 2, 2, A_KM, B_KM, OutT>(op, A, B, st);
     return launch<64, 64, 2, 2, 2, A_KM, B_KM, OutT>(op, A, B, st);
 }
 
