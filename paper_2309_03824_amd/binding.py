@@ -20,6 +20,7 @@ F32, BF16 = 0, 1
 KIND_SVD, KIND_TUCKER = 0, 1
 FREEZE_L0, FREEZE_L1, FREEZE_L2 = 1, 2, 4
 FUSION_AUTO, FUSION_ALWAYS, FUSION_NEVER = 0, 1, 2
+ROLE_NONE, ROLE_FWD_DOWN, ROLE_FWD_UP, ROLE_DGRAD_UP, ROLE_DGRAD_DOWN, ROLE_WGRAD_U, ROLE_WGRAD_V = range(7)
 ROUND_NEAREST, ROUND_DOWN, ROUND_UP = 0, 1, 2
 
 EXPORTS = (
@@ -28,7 +29,7 @@ EXPORTS = (
     "lrd_dense_linear_workspace_bytes", "lrd_dense_linear_fwd", "lrd_dense_linear_bwd",
     "lrd_tucker_conv_workspace_bytes", "lrd_tucker_conv_fwd", "lrd_tucker_conv_bwd",
     "lrd_dense_conv_workspace_bytes", "lrd_dense_conv_fwd", "lrd_dense_conv_bwd",
-    "lrd_gelu_fwd", "lrd_gelu_bwd", "lrd_set_fusion",
+    "lrd_gelu_fwd", "lrd_gelu_bwd", "lrd_set_fusion", "lrd_profile_next",
 )
 
 
@@ -90,6 +91,8 @@ def _load() -> ctypes.CDLL:
     lib.lrd_dense_conv_bwd.argtypes = [P] * 5 + [G, ctypes.c_int, P, SZ, P]
     lib.lrd_gelu_fwd.restype = ctypes.c_int
     lib.lrd_gelu_fwd.argtypes = [P, P, I64, ctypes.c_int, P]
+    lib.lrd_profile_next.restype = ctypes.c_int
+    lib.lrd_profile_next.argtypes = [c_int32, P, P]
     lib.lrd_set_fusion.restype = c_int32
     lib.lrd_set_fusion.argtypes = [c_int32]
     lib.lrd_gelu_bwd.restype = ctypes.c_int
@@ -169,6 +172,38 @@ def set_fusion(mode: int) -> int:
     if prev < 0:
         raise LrdError(ERR_INVALID_ARG, "lrd_set_fusion")
     return prev
+
+
+class HipEvent:
+    """A raw hipEvent_t (created through the HIP runtime), for lrd_profile_next."""
+    _hip = None
+
+    def __init__(self):
+        if HipEvent._hip is None:
+            HipEvent._hip = ctypes.CDLL("libamdhip64.so")
+            HipEvent._hip.hipEventCreate.argtypes = [POINTER(c_void_p)]
+            HipEvent._hip.hipEventElapsedTime.argtypes = [POINTER(ctypes.c_float), c_void_p, c_void_p]
+            HipEvent._hip.hipEventDestroy.argtypes = [c_void_p]
+        self.handle = c_void_p()
+        if HipEvent._hip.hipEventCreate(ctypes.byref(self.handle)) != 0:
+            raise RuntimeError("hipEventCreate failed")
+
+    def elapsed_us(self, later: "HipEvent") -> float:
+        ms = ctypes.c_float()
+        if HipEvent._hip.hipEventElapsedTime(ctypes.byref(ms), self.handle, later.handle) != 0:
+            raise RuntimeError("hipEventElapsedTime failed (events not complete?)")
+        return ms.value * 1e3
+
+    def __del__(self):
+        try:
+            HipEvent._hip.hipEventDestroy(self.handle)
+        except Exception:
+            pass
+
+
+def profile_next(role: int, start: HipEvent = None, stop: HipEvent = None):
+    _check(_lib.lrd_profile_next(role, start.handle if start else None, stop.handle if stop else None),
+           "lrd_profile_next")
 
 
 # ------------------------------------------------------------------------------- linear pair

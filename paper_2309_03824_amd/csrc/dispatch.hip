@@ -1,4 +1,6 @@
 // Engine selection for a single matrix product and the split-K policy.
+#include <atomic>
+
 #include "lrd_internal.hpp"
 
 namespace lrd {
@@ -17,11 +19,40 @@ int choose_splits(int64_t M, int64_t N, int64_t K, bool in_bf16)
     return s < 2 ? 1 : (int)s;
 }
 
+namespace {
+std::atomic<int> g_probe_role{0};
+hipEvent_t g_probe_start = nullptr, g_probe_stop = nullptr;
+}  // namespace
+
+void probe_arm(int role, hipEvent_t start, hipEvent_t stop)
+{
+    g_probe_role.store(0);
+    g_probe_start = start;
+    g_probe_stop = stop;
+    g_probe_role.store(role);
+}
+
+bool probe_take(int role, hipEvent_t* start, hipEvent_t* stop)
+{
+    if (role == 0) return false;
+    int expected = role;
+    if (!g_probe_role.compare_exchange_strong(expected, 0)) return false;
+    *start = g_probe_start;
+    *stop = g_probe_stop;
+    return true;
+}
+
 hipError_t run_matop(const MatOp& op, hipStream_t st)
 {
-    if (mfma_gemm2_supported(op)) return mfma_gemm2(op, st);
-    if (mfma_matop_supported(op)) return mfma_matop(op, st);
-    return generic_matop(op, st);
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    const bool probed = probe_take(op.role, &ev0, &ev1);
+    if (probed) (void)hipEventRecord(ev0, st);
+    hipError_t e;
+    if (mfma_gemm2_supported(op)) e = mfma_gemm2(op, st);
+    else if (mfma_matop_supported(op)) e = mfma_matop(op, st);
+    else e = generic_matop(op, st);
+    if (probed) (void)hipEventRecord(ev1, st);
+    return e;
 }
 
 }  // namespace lrd

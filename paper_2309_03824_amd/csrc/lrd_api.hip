@@ -22,6 +22,16 @@ inline bool want_fusion(const ChainOp& ch)
     return mode == LRD_FUSION_ALWAYS;
 }
 
+hipError_t run_chain(const ChainOp& ch, hipStream_t st)
+{
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    const bool probed = probe_take(ch.role, &ev0, &ev1);
+    if (probed) (void)hipEventRecord(ev0, st);
+    hipError_t e = mfma_chain(ch, st);
+    if (probed) (void)hipEventRecord(ev1, st);
+    return e;
+}
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round256(size_t b) { return (b + 255) & ~size_t(255); }
 inline size_t esize(lrd_dtype dt) { return dt == LRD_BF16 ? 2 : 4; }
@@ -140,6 +150,14 @@ int32_t lrd_set_fusion(int32_t mode)
     return g_fusion.exchange(mode);
 }
 
+lrd_status lrd_profile_next(int32_t role, void* start_event, void* stop_event)
+{
+    if (role < LRD_ROLE_NONE || role > LRD_ROLE_WGRAD_V) return LRD_ERR_INVALID_ARG;
+    if (role != LRD_ROLE_NONE && (!start_event || !stop_event)) return LRD_ERR_INVALID_ARG;
+    probe_arm(role, (hipEvent_t)start_event, (hipEvent_t)stop_event);
+    return LRD_OK;
+}
+
 // ------------------------------------------------------------------------------------ linear
 size_t lrd_linear_workspace_bytes(int64_t T, int64_t in, int64_t out, int64_t r, lrd_dtype dt,
                                   uint32_t freeze_mask)
@@ -171,8 +189,9 @@ lrd_status lrd_linear_fwd(const void* X, const void* V, const void* U, const flo
         ch.mid_save = H_save; ch.ldmid = r;
         ch.bias = bias;
         ch.M = T; ch.K1 = in; ch.R = r; ch.N2 = out;
+        ch.role = LRD_ROLE_FWD_DOWN;
         if (want_fusion(ch)) {
-            LRD_TRY(mfma_chain(ch, st));
+            LRD_TRY(run_chain(ch, st));
             return LRD_OK;
         }
     }
@@ -182,6 +201,8 @@ lrd_status lrd_linear_fwd(const void* X, const void* V, const void* U, const flo
     MatOp g1 = nt(X, in, V, in, H, r, T, r, in, dt, false);
     MatOp g2 = nt(H, r, U, r, Y, out, T, out, r, dt, false);
     g2.bias = bias;
+    g1.role = LRD_ROLE_FWD_DOWN;
+    g2.role = LRD_ROLE_FWD_UP;
     LRD_TRY(run_matop(g1, st));
     LRD_TRY(run_matop(g2, st));
     return LRD_OK;
@@ -211,10 +232,12 @@ lrd_status lrd_linear_bwd(const void* dY, const void* X, const void* H, const vo
     MatOp wu, wv;
     if (train_u) {
         wu = tn(dY, out, H ? H : Hre, r, dU, r, out, r, T, dt);
+        wu.role = LRD_ROLE_WGRAD_U;
         attach_splits(wu, cv, dt);
     }
     if (train_v) {
         wv = tn(dH, r, X, in, dV, in, r, in, T, dt);
+        wv.role = LRD_ROLE_WGRAD_V;
         // the two weight-gradient products run one after the other and may share partials
         if (train_u && wu.partial) {
             int s = choose_splits(wv.M, wv.N, wv.K, dt == LRD_BF16);
@@ -237,14 +260,21 @@ lrd_status lrd_linear_bwd(const void* dY, const void* X, const void* H, const vo
             ch.C = dX; ch.ldc = in;
             ch.mid_save = train_v ? dH : nullptr; ch.ldmid = r;
             ch.M = T; ch.K1 = out; ch.R = r; ch.N2 = in;
+            ch.role = LRD_ROLE_DGRAD_UP;
             if (want_fusion(ch)) {
-                LRD_TRY(mfma_chain(ch, st));
+                LRD_TRY(run_chain(ch, st));
                 fused = true;
             }
         }
         if (!fused) {
-            LRD_TRY(run_matop(nn(dY, out, U, r, dH, r, T, r, out, dt), st));
-            if (dX) LRD_TRY(run_matop(nn(dH, r, V, in, dX, in, T, in, r, dt), st));
+            MatOp d1 = nn(dY, out, U, r, dH, r, T, r, out, dt);
+            d1.role = LRD_ROLE_DGRAD_UP;
+            LRD_TRY(run_matop(d1, st));
+            if (dX) {
+                MatOp d2 = nn(dH, r, V, in, dX, in, T, in, r, dt);
+                d2.role = LRD_ROLE_DGRAD_DOWN;
+                LRD_TRY(run_matop(d2, st));
+            }
         }
     }
     if (train_u) {

@@ -35,6 +35,7 @@ struct MatOp {
     // sums the slices in a fixed order into C, so results do not depend on scheduling.
     int splits = 1;
     float* partial = nullptr;
+    int role = 0;           // which product of a layer pass this is (for the event probe)
 };
 
 // Engines.  Each returns hipSuccess or the launch error.
@@ -58,9 +59,14 @@ struct ChainOp {
     void* mid_save = nullptr; int64_t ldmid = 0;
     const float* bias = nullptr;
     int64_t M = 0, K1 = 0, R = 0, N2 = 0;
+    int role = 0;
 };
 bool mfma_chain_supported(const ChainOp& op);
 hipError_t mfma_chain(const ChainOp& op, hipStream_t st);
+
+// One-shot event probe (lrd_profile_next): returns true and hands out the events if armed for role.
+void probe_arm(int role, hipEvent_t start, hipEvent_t stop);
+bool probe_take(int role, hipEvent_t* start, hipEvent_t* stop);
 
 // Elementwise / reductions.
 hipError_t gelu_fwd(const void* Z, void* A, int64_t n, bool bf16, hipStream_t st);
