@@ -7,7 +7,8 @@ of 64); tokens = batch 32 x seq 256 = 8192, bf16 activations ~ N(0,1); the freez
 is Algorithm 2's mask for epoch s (V frozen on even steps, U frozen on odd steps).
 
 Prints ONE JSON line.  `value` is the algorithmic TFLOP/s of the decomposed layers (FLOPs as
-masked by freezing; GELU glue time is inside the step but adds no FLOPs to the numerator), with
+masked by freezing; the GELU between the two linears is folded into the pair kernels' epilogues,
+its time is inside the step and it adds no FLOPs to the numerator), with
 all inputs resident in HBM before the timed region.  Extra fields: tokens/s, the dense
 (undecomposed) stack and the unquantized-rank/unfrozen stack timed in the same run, the roofline
 of the dominant kernel, and the CPU oracle's rate on a bounded sample.
@@ -71,7 +72,6 @@ class Stack:
         self.Z = [torch.empty((T, D_FF), dtype=bf, device=dev) for _ in range(N_BLOCKS)]
         self.A = [torch.empty((T, D_FF), dtype=bf, device=dev) for _ in range(N_BLOCKS)]
         self.gX = [torch.empty((T, D_MODEL), dtype=bf, device=dev) for _ in range(2)]
-        self.gA = torch.empty((T, D_FF), dtype=bf, device=dev)
         self.gZ = torch.empty((T, D_FF), dtype=bf, device=dev)
         nbytes = max(lrd.linear_workspace_bytes(T, D_MODEL, D_FF, rank, lrd.BF16, 0),
                      lrd.linear_workspace_bytes(T, D_FF, D_MODEL, rank, lrd.BF16, 0))
@@ -89,8 +89,7 @@ class Stack:
         lrd = self.lrd
         for b, (l1, l2) in enumerate(self.layers):
             self._probe()
-            lrd.linear_fwd(self.X[b], l1["V"], l1["U"], None, self.Z[b], l1["H"], self.ws)
-            lrd.gelu_fwd(self.Z[b], self.A[b])
+            lrd.linear_fwd_act(self.X[b], l1["V"], l1["U"], None, self.Z[b], self.A[b], l1["H"], lrd.ACT_GELU, self.ws)
             self._probe()
             lrd.linear_fwd(self.A[b], l2["V"], l2["U"], None, self.X[b + 1], l2["H"], self.ws)
 
@@ -101,8 +100,8 @@ class Stack:
         for b in reversed(range(N_BLOCKS)):
             l1, l2 = self.layers[b]
             out = self.gX[b & 1]
-            lrd.linear_bwd(g, self.A[b], l2["H"], l2["V"], l2["U"], self.gA, l2["dV"], l2["dU"], None, mask, self.ws)
-            lrd.gelu_bwd(self.gA, self.Z[b], self.gZ)
+            lrd.linear_bwd_act(g, self.A[b], l2["H"], l2["V"], l2["U"], self.gZ, l2["dV"], l2["dU"], None, mask,
+                               self.Z[b], lrd.ACT_GELU, self.ws)
             lrd.linear_bwd(self.gZ, self.X[b], l1["H"], l1["V"], l1["U"], out if b > 0 else None,
                            l1["dV"], l1["dU"], None, mask, self.ws)
             g = out

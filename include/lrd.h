@@ -143,6 +143,28 @@ lrd_status lrd_linear_bwd(const void* dY, const void* X, const void* H, const vo
                           lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * The same two calls with the activation between stacked layers folded into them (GELU, erf
+ * form; not part of the paper's method, it removes two elementwise passes of a layer stack).
+ *   lrd_linear_fwd_act: Y receives the pre-activation Z = H.U^T (+ bias), which the backward
+ *     needs, and Y_act [T x out] receives act(Z) as rounded to the activation dtype.
+ *   lrd_linear_bwd_act: for a layer whose input X is act(Z_in), Z_in [T x in] being the
+ *     pre-activation saved by the previous layer's forward: dX receives (dH.V) * act'(Z_in),
+ *     i.e. the gradient with respect to Z_in.  Z_in is required iff dX is given.
+ * act = LRD_ACT_NONE makes them identical to the plain calls (Y_act / Z_in ignored).  Results are
+ * bit-identical to the plain call followed by lrd_gelu_fwd / lrd_gelu_bwd.
+ */
+enum { LRD_ACT_NONE = 0, LRD_ACT_GELU = 1 };
+lrd_status lrd_linear_fwd_act(const void* X, const void* V, const void* U, const float* bias,
+                              void* Y, void* Y_act, void* H_save, int32_t act, int64_t T,
+                              int64_t in, int64_t out, int64_t r, lrd_dtype dt, void* ws,
+                              size_t ws_bytes, void* hip_stream);
+lrd_status lrd_linear_bwd_act(const void* dY, const void* X, const void* H, const void* V,
+                              const void* U, void* dX, float* dV, float* dU, float* dbias,
+                              uint32_t freeze_mask, const void* Z_in, int32_t act, int64_t T,
+                              int64_t in, int64_t out, int64_t r, lrd_dtype dt, void* ws,
+                              size_t ws_bytes, void* hip_stream);
+
+/*
  * The undecomposed layer Y = X.W^T (+ bias), dX = dY.W, dW = dY^T.X: the "original layer" whose
  * time Algorithm 1 compares a decomposed layer against.  W [out x in]; dX, dW nullable.
  */

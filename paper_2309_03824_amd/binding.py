@@ -22,10 +22,11 @@ FREEZE_L0, FREEZE_L1, FREEZE_L2 = 1, 2, 4
 FUSION_AUTO, FUSION_ALWAYS, FUSION_NEVER = 0, 1, 2
 ROLE_NONE, ROLE_FWD_DOWN, ROLE_FWD_UP, ROLE_DGRAD_UP, ROLE_DGRAD_DOWN, ROLE_WGRAD_U, ROLE_WGRAD_V = range(7)
 ROUND_NEAREST, ROUND_DOWN, ROUND_UP = 0, 1, 2
+ACT_NONE, ACT_GELU = 0, 1
 
 EXPORTS = (
     "lrd_status_string", "lrd_quantize_rank", "lrd_freeze_mask", "lrd_tucker_rank", "lrd_svd_rank",
-    "lrd_linear_workspace_bytes", "lrd_linear_fwd", "lrd_linear_bwd",
+    "lrd_linear_workspace_bytes", "lrd_linear_fwd", "lrd_linear_bwd", "lrd_linear_fwd_act", "lrd_linear_bwd_act",
     "lrd_dense_linear_workspace_bytes", "lrd_dense_linear_fwd", "lrd_dense_linear_bwd",
     "lrd_tucker_conv_workspace_bytes", "lrd_tucker_conv_fwd", "lrd_tucker_conv_bwd",
     "lrd_dense_conv_workspace_bytes", "lrd_dense_conv_fwd", "lrd_dense_conv_bwd",
@@ -71,6 +72,10 @@ def _load() -> ctypes.CDLL:
     lib.lrd_linear_fwd.argtypes = [P] * 6 + [I64] * 4 + [ctypes.c_int, P, SZ, P]
     lib.lrd_linear_bwd.restype = ctypes.c_int
     lib.lrd_linear_bwd.argtypes = [P] * 9 + [U32] + [I64] * 4 + [ctypes.c_int, P, SZ, P]
+    lib.lrd_linear_fwd_act.restype = ctypes.c_int
+    lib.lrd_linear_fwd_act.argtypes = [P] * 7 + [c_int32] + [I64] * 4 + [ctypes.c_int, P, SZ, P]
+    lib.lrd_linear_bwd_act.restype = ctypes.c_int
+    lib.lrd_linear_bwd_act.argtypes = [P] * 9 + [U32, P, c_int32] + [I64] * 4 + [ctypes.c_int, P, SZ, P]
     lib.lrd_dense_linear_workspace_bytes.restype = SZ
     lib.lrd_dense_linear_workspace_bytes.argtypes = [I64] * 3 + [ctypes.c_int]
     lib.lrd_dense_linear_fwd.restype = ctypes.c_int
@@ -229,6 +234,24 @@ def linear_bwd(dY, X, H, V, U, dX, dV, dU, dbias, freeze_mask, ws=None, stream=N
     _check(_lib.lrd_linear_bwd(_ptr(dY), _ptr(X), _ptr(H), _ptr(V), _ptr(U), _ptr(dX), _ptr(dV), _ptr(dU),
                                _ptr(dbias), freeze_mask, T, n_in, n_out, r, _dt(dY), wp, wb, _stream(stream)),
            "lrd_linear_bwd")
+
+
+def linear_fwd_act(X, V, U, bias, Y, Y_act, H_save, act, ws=None, stream=None):
+    T, n_in = X.shape
+    r, n_out = V.shape[0], U.shape[0]
+    assert V.shape == (r, n_in) and U.shape == (n_out, r) and Y.shape == (T, n_out)
+    wp, wb = _ws(ws)
+    _check(_lib.lrd_linear_fwd_act(_ptr(X), _ptr(V), _ptr(U), _ptr(bias), _ptr(Y), _ptr(Y_act), _ptr(H_save), act,
+                                   T, n_in, n_out, r, _dt(X), wp, wb, _stream(stream)), "lrd_linear_fwd_act")
+
+
+def linear_bwd_act(dY, X, H, V, U, dX, dV, dU, dbias, freeze_mask, Z_in, act, ws=None, stream=None):
+    T, n_out = dY.shape
+    r, n_in = V.shape
+    wp, wb = _ws(ws)
+    _check(_lib.lrd_linear_bwd_act(_ptr(dY), _ptr(X), _ptr(H), _ptr(V), _ptr(U), _ptr(dX), _ptr(dV), _ptr(dU),
+                                   _ptr(dbias), freeze_mask, _ptr(Z_in), act, T, n_in, n_out, r, _dt(dY), wp, wb,
+                                   _stream(stream)), "lrd_linear_bwd_act")
 
 
 def dense_linear_workspace_bytes(T, n_in, n_out, dtype) -> int:

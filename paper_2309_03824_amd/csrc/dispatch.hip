@@ -42,17 +42,33 @@ bool probe_take(int role, hipEvent_t* start, hipEvent_t* stop)
     return true;
 }
 
+// The activation epilogue as separate elementwise passes, for engines that do not fuse it.
+// C and aux are dense [M x N] here (ldc = ldaux = N), which is all the layer passes produce.
+hipError_t apply_epilogue(const MatOp& op, hipStream_t st)
+{
+    if (op.ldc != op.N || op.ldaux != op.N) return hipErrorInvalidValue;
+    const int64_t n = op.M * op.N;
+    if (op.epilogue == EPI_ACT_STORE) return gelu_fwd(op.C, op.aux, n, op.in_bf16, st);
+    if (op.epilogue == EPI_ACT_GRAD) return gelu_bwd(op.C, op.aux, op.C, n, op.in_bf16, st);
+    return hipSuccess;
+}
+
 hipError_t run_matop(const MatOp& op, hipStream_t st)
 {
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     const bool probed = probe_take(op.role, &ev0, &ev1);
     if (probed) (void)hipEventRecord(ev0, st);
     hipError_t e;
+    bool epilogue_done = true;
     if (mfma_gemm2_supported(op)) e = mfma_gemm2(op, st);
-    else if (mfma_matop_supported(op)) e = mfma_matop(op, st);
-    else e = generic_matop(op, st);
+    else {
+        epilogue_done = op.epilogue == EPI_NONE;
+        if (mfma_matop_supported(op)) e = mfma_matop(op, st);
+        else e = generic_matop(op, st);
+    }
     if (probed) (void)hipEventRecord(ev1, st);
-    return e;
+    if (e != hipSuccess || epilogue_done) return e;
+    return apply_epilogue(op, st);
 }
 
 }  // namespace lrd

@@ -5,15 +5,6 @@
 namespace lrd {
 namespace {
 
-__device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.f + erff(z * 0.70710678118654752f)); }
-
-__device__ __forceinline__ float gelu_grad_f(float z)
-{
-    float Phi = 0.5f * (1.f + erff(z * 0.70710678118654752f));
-    float phi = 0.39894228040143268f * __expf(-0.5f * z * z);
-    return Phi + z * phi;
-}
-
 // 8 bf16 (16 bytes) per thread per step; n8 = number of whole groups of 8.
 __global__ __launch_bounds__(256) void gelu_fwd_bf16(const bf16_t* __restrict__ Z, bf16_t* __restrict__ A, int64_t n)
 {
@@ -32,8 +23,8 @@ __global__ __launch_bounds__(256) void gelu_fwd_bf16(const bf16_t* __restrict__ 
     }
 }
 
-__global__ __launch_bounds__(256) void gelu_bwd_bf16(const bf16_t* __restrict__ dA, const bf16_t* __restrict__ Z,
-                                                     bf16_t* __restrict__ dZ, int64_t n)
+__global__ __launch_bounds__(256) void gelu_bwd_bf16(const bf16_t* dA, const bf16_t* __restrict__ Z,
+                                                     bf16_t* dZ, int64_t n)   // dZ may alias dA
 {
     int64_t n8 = n / 8;
     int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -57,8 +48,8 @@ __global__ __launch_bounds__(256) void gelu_fwd_f32(const float* __restrict__ Z,
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) A[i] = gelu_f(Z[i]);
 }
 
-__global__ __launch_bounds__(256) void gelu_bwd_f32(const float* __restrict__ dA, const float* __restrict__ Z,
-                                                    float* __restrict__ dZ, int64_t n)
+__global__ __launch_bounds__(256) void gelu_bwd_f32(const float* dA, const float* __restrict__ Z,
+                                                    float* dZ, int64_t n)   // dZ may alias dA
 {
     int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)

@@ -174,9 +174,19 @@ lrd_status lrd_linear_fwd(const void* X, const void* V, const void* U, const flo
                           void* H_save, int64_t T, int64_t in, int64_t out, int64_t r,
                           lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream)
 {
+    return lrd_linear_fwd_act(X, V, U, bias, Y, nullptr, H_save, LRD_ACT_NONE, T, in, out, r, dt, ws, ws_bytes,
+                              hip_stream);
+}
+
+lrd_status lrd_linear_fwd_act(const void* X, const void* V, const void* U, const float* bias, void* Y,
+                              void* Y_act, void* H_save, int32_t act, int64_t T, int64_t in, int64_t out,
+                              int64_t r, lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream)
+{
     if (!dtype_ok(dt) || !linear_dims_ok(T, in, out, r) || !X || !V || !U || !Y) return LRD_ERR_INVALID_ARG;
+    if ((act != LRD_ACT_NONE && act != LRD_ACT_GELU) || (act == LRD_ACT_GELU && !Y_act)) return LRD_ERR_INVALID_ARG;
+    if (act == LRD_ACT_NONE) Y_act = nullptr;
     if (!aligned16(X) || !aligned16(V) || !aligned16(U) || !aligned16(Y) || !aligned16(H_save) || !aligned16(ws) ||
-        !aligned16(bias))
+        !aligned16(bias) || !aligned16(Y_act))
         return LRD_ERR_ALIGNMENT;
     hipStream_t st = (hipStream_t)hip_stream;
 
@@ -192,6 +202,7 @@ lrd_status lrd_linear_fwd(const void* X, const void* V, const void* U, const flo
         ch.role = LRD_ROLE_FWD_DOWN;
         if (want_fusion(ch)) {
             LRD_TRY(run_chain(ch, st));
+            if (Y_act) LRD_TRY(gelu_fwd(Y, Y_act, T * out, true, st));
             return LRD_OK;
         }
     }
@@ -203,6 +214,11 @@ lrd_status lrd_linear_fwd(const void* X, const void* V, const void* U, const flo
     g2.bias = bias;
     g1.role = LRD_ROLE_FWD_DOWN;
     g2.role = LRD_ROLE_FWD_UP;
+    if (Y_act) {
+        g2.epilogue = EPI_ACT_STORE;
+        g2.aux = Y_act;
+        g2.ldaux = out;
+    }
     LRD_TRY(run_matop(g1, st));
     LRD_TRY(run_matop(g2, st));
     return LRD_OK;
@@ -213,7 +229,19 @@ lrd_status lrd_linear_bwd(const void* dY, const void* X, const void* H, const vo
                           uint32_t freeze_mask, int64_t T, int64_t in, int64_t out, int64_t r,
                           lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream)
 {
+    return lrd_linear_bwd_act(dY, X, H, V, U, dX, dV, dU, dbias, freeze_mask, nullptr, LRD_ACT_NONE, T, in, out, r,
+                              dt, ws, ws_bytes, hip_stream);
+}
+
+lrd_status lrd_linear_bwd_act(const void* dY, const void* X, const void* H, const void* V,
+                              const void* U, void* dX, float* dV, float* dU, float* dbias,
+                              uint32_t freeze_mask, const void* Z_in, int32_t act, int64_t T, int64_t in,
+                              int64_t out, int64_t r, lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream)
+{
     if (!dtype_ok(dt) || !linear_dims_ok(T, in, out, r) || !dY || !V || !U) return LRD_ERR_INVALID_ARG;
+    if ((act != LRD_ACT_NONE && act != LRD_ACT_GELU) || (act == LRD_ACT_GELU && dX && !Z_in)) return LRD_ERR_INVALID_ARG;
+    if (act == LRD_ACT_NONE || !dX) Z_in = nullptr;
+    if (!aligned16(Z_in)) return LRD_ERR_ALIGNMENT;
     if (freeze_mask & ~uint32_t(LRD_FREEZE_L0 | LRD_FREEZE_L1)) return LRD_ERR_INVALID_ARG;
     const bool train_v = !(freeze_mask & LRD_FREEZE_L0), train_u = !(freeze_mask & LRD_FREEZE_L1);
     if (train_v && (!dV || !X)) return LRD_ERR_INVALID_ARG;
@@ -223,12 +251,12 @@ lrd_status lrd_linear_bwd(const void* dY, const void* X, const void* H, const vo
         return LRD_ERR_ALIGNMENT;
     hipStream_t st = (hipStream_t)hip_stream;
     Carver cv(ws, ws_bytes);
-    const size_t act = (size_t)T * r * esize(dt);
+    const size_t act_bytes = (size_t)T * r * esize(dt);
     const bool need_dH = dX || train_v;
 
     // Carve everything first so that a short workspace is reported before any launch.
-    void* dH = need_dH ? cv.take(act) : nullptr;
-    void* Hre = (train_u && !H) ? cv.take(act) : nullptr;
+    void* dH = need_dH ? cv.take(act_bytes) : nullptr;
+    void* Hre = (train_u && !H) ? cv.take(act_bytes) : nullptr;
     MatOp wu, wv;
     if (train_u) {
         wu = tn(dY, out, H ? H : Hre, r, dU, r, out, r, T, dt);
@@ -263,6 +291,7 @@ lrd_status lrd_linear_bwd(const void* dY, const void* X, const void* H, const vo
             ch.role = LRD_ROLE_DGRAD_UP;
             if (want_fusion(ch)) {
                 LRD_TRY(run_chain(ch, st));
+                if (Z_in) LRD_TRY(gelu_bwd(dX, Z_in, dX, T * in, true, st));
                 fused = true;
             }
         }
@@ -273,6 +302,11 @@ lrd_status lrd_linear_bwd(const void* dY, const void* X, const void* H, const vo
             if (dX) {
                 MatOp d2 = nn(dH, r, V, in, dX, in, T, in, r, dt);
                 d2.role = LRD_ROLE_DGRAD_DOWN;
+                if (Z_in) {
+                    d2.epilogue = EPI_ACT_GRAD;
+                    d2.aux = const_cast<void*>(Z_in);
+                    d2.ldaux = in;
+                }
                 LRD_TRY(run_matop(d2, st));
             }
         }

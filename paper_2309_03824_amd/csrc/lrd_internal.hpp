@@ -36,7 +36,14 @@ struct MatOp {
     int splits = 1;
     float* partial = nullptr;
     int role = 0;           // which product of a layer pass this is (for the event probe)
+    // Optional GELU epilogue (bf16 results on the aligned MFMA path only; see epilogue_fusable):
+    //   EPI_ACT_STORE: aux[m][n] = gelu(C[m][n]) is written next to C (C keeps the pre-activation);
+    //   EPI_ACT_GRAD : C[m][n] is multiplied by gelu'(aux[m][n]) (aux = pre-activation, read).
+    int epilogue = 0;
+    void* aux = nullptr;
+    int64_t ldaux = 0;
 };
+enum { EPI_NONE = 0, EPI_ACT_STORE = 1, EPI_ACT_GRAD = 2 };
 
 // Engines.  Each returns hipSuccess or the launch error.
 hipError_t generic_matop(const MatOp& op, hipStream_t st);          // any MatOp, plain FMA tiles
@@ -45,6 +52,7 @@ hipError_t mfma_matop(const MatOp& op, hipStream_t st);
 bool mfma_gemm2_supported(const MatOp& op);                        // aligned fast path covers it?
 hipError_t mfma_gemm2(const MatOp& op, hipStream_t st);
 hipError_t run_matop(const MatOp& op, hipStream_t st);              // picks an engine
+hipError_t apply_epilogue(const MatOp& op, hipStream_t st);        // unfused form of MatOp::epilogue
 
 // Workspace floats a MatOp of this shape needs for split-K (0 if it will not be split).
 int choose_splits(int64_t M, int64_t N, int64_t K, bool in_bf16);

@@ -185,7 +185,8 @@ constexpr int gemm2_lds_bytes()
 template <int BM, int BN, int WGM, int WGN, int DEPTH, bool A_KM, bool B_KM, class OutT>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm2_kernel(Operand A, Operand B, OutT* __restrict__ C, int64_t ldc,
                                                                const float* __restrict__ bias, float* __restrict__ partial,
-                                                               int M, int N, int K, int k_per_split)
+                                                               int M, int N, int K, int k_per_split, int epilogue,
+                                                               bf16_t* __restrict__ aux, int64_t ldaux)
 {
     constexpr int NT = 64 * WGM * WGN;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
@@ -268,6 +269,20 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm2_kernel(Operand A, Operan
     } else {
         // bf16 results: registers -> LDS tile (row-major) -> 16 contiguous bytes per lane to global memory
         constexpr int LDC = BN + 8;
+        constexpr int CPR = BN / 8;
+        constexpr int PER = BM * CPR / NT;          // 16-byte chunks per thread
+        bf16_t* out = reinterpret_cast<bf16_t*>(C);
+        // The activation-gradient epilogue reads the pre-activation: start those loads now, so they
+        // are in flight while the accumulators go through LDS.
+        bf16x8 z8[PER];
+        if (epilogue == EPI_ACT_GRAD) {
+#pragma unroll
+            for (int q = 0; q < PER; ++q) {
+                int c = tid + q * NT;
+                int m = min(m0 + c / CPR, M - 1), n = min(n0 + (c % CPR) * 8, N - 8);
+                z8[q] = *reinterpret_cast<const bf16x8*>(aux + (int64_t)m * ldaux + n);
+            }
+        }
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             int ml = wm * WTM + i * 32 + r;
@@ -287,15 +302,25 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm2_kernel(Operand A, Operan
                 }
         }
         __syncthreads();
-        constexpr int CPR = BN / 8;
-        bf16_t* out = reinterpret_cast<bf16_t*>(C);
-#pragma unroll 4
-        for (int c = tid; c < BM * CPR; c += NT) {
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            int c = tid + q * NT;
             int ml = c / CPR, cc = c % CPR;
             int m = m0 + ml, n = n0 + cc * 8;
-            if (m < M && n < N) {   // N is a multiple of 8 on this path
-                u32x4 v = *reinterpret_cast<const u32x4*>(lds + ml * LDC + cc * 8);
-                *reinterpret_cast<u32x4*>(out + (int64_t)m * ldc + n) = v;
+            const bool ok = m < M && n < N;   // N is a multiple of 8 on this path
+            u32x4 v = *reinterpret_cast<const u32x4*>(lds + ml * LDC + cc * 8);
+            if (epilogue == EPI_ACT_GRAD) {
+                bf16x8 c8 = __builtin_bit_cast(bf16x8, v);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) c8[e] = (bf16_t)((float)c8[e] * gelu_grad_f((float)z8[q][e]));
+                v = __builtin_bit_cast(u32x4, c8);
+            }
+            if (ok) *reinterpret_cast<u32x4*>(out + (int64_t)m * ldc + n) = v;
+            if (epilogue == EPI_ACT_STORE) {
+                bf16x8 c8 = __builtin_bit_cast(bf16x8, v);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) c8[e] = (bf16_t)gelu_f((float)c8[e]);
+                if (ok) *reinterpret_cast<bf16x8*>(aux + (int64_t)m * ldaux + n) = c8;
             }
         }
     }
@@ -320,7 +345,7 @@ hipError_t launch(const MatOp& op, const Operand& A, const Operand& B, hipStream
     float* partial = splits > 1 ? op.partial : nullptr;
     dim3 grid((unsigned)ceil_div(op.M, BM), (unsigned)ceil_div(op.N, BN), (unsigned)splits);
     hipLaunchKernelGGL(kern, grid, dim3(NT), lds_bytes, st, A, B, (OutT*)op.C, op.ldc, op.bias, partial, (int)op.M,
-                       (int)op.N, (int)op.K, kps);
+                       (int)op.N, (int)op.K, kps, op.epilogue, (bf16_t*)op.aux, op.ldaux);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (splits > 1) return reduce_partials(op.partial, (float*)op.C, op.ldc, op.M, op.N, splits, st);
@@ -366,6 +391,7 @@ bool mfma_gemm2_supported(const MatOp& op)
         if (op.bias && (op.N < 4 || (reinterpret_cast<uintptr_t>(op.bias) & 15u))) return false;
     }
     if (ceil_div(op.N, 64) > 65535) return false;
+    if (op.epilogue != EPI_NONE && (op.out_f32 || !op.aux || !al16(op.aux) || op.ldaux % 8 != 0)) return false;
     return true;
 }
 

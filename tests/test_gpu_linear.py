@@ -142,6 +142,14 @@ def test_ffn_block_shapes_full_size_bf16():
                    factors=(U, V))
 
 
+def test_transformer_projection_shapes_bf16():
+    """Encoder with hidden 1024 / FFN 4096 at rank 256: the Q/K/V/O shape (1024 -> 1024) at the full
+    8192 tokens, the two FFN shapes on a 1024-token slice, masks cycling with the step."""
+    r = lrd.quantize_rank(256, 64)
+    for step, (T, n_in, n_out) in enumerate(((8192, 1024, 1024), (1024, 1024, 4096), (1024, 4096, 1024))):
+        run_linear(T, n_in, n_out, r, "bf16", lrd.freeze_mask(lrd.KIND_SVD, step), seed=500 + step)
+
+
 def test_large_layer_sampled_bf16():
     """4096 x 4096 layer, 16384 tokens, rank 256: the oracle evaluates sampled token rows of Y/H/dX
     and the weight gradients of a gradient that is non-zero on sampled tokens only."""
@@ -204,6 +212,36 @@ def test_gelu(dt):
         torch.cuda.synchronize()
         check(host(A_), oracle.gelu_fwd(seen(Z, dt)), dt, "gelu")
         check(host(dZ_), oracle.gelu_bwd(seen(dA, dt), seen(Z, dt)), dt, "gelu bwd")
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+@pytest.mark.parametrize("shape", [(384, 256, 512, 64), (130, 72, 88, 24), (257, 96, 520, 33)])
+def test_activation_folded_into_the_pair(dt, shape):
+    """lrd_linear_fwd_act / lrd_linear_bwd_act against the plain calls followed by the GELU kernels
+    (bit-identical) and against the oracle: Z = pair(X), A = gelu(Z); dZ_in = (dH V) * gelu'(Z_in)."""
+    T, n_in, n_out, r = shape
+    rng = np.random.Generator(np.random.PCG64(sum(shape)))
+    X, dY, Zin = si.gaussian((T, n_in), rng), si.gaussian((T, n_out), rng), si.gaussian((T, n_in), rng)
+    U, V = si.direct_factors(n_out, n_in, r, rng)
+    X_, V_, U_, dY_, Zin_ = (dev(a, dt) for a in (X, V, U, dY, Zin))
+    ws = workspace(lrd.linear_workspace_bytes(T, n_in, n_out, r, code(dt), 0))
+    Z1, A1, Z2, A2 = (empty((T, n_out), dt) for _ in range(4))
+    H1, H2 = empty((T, r), dt), empty((T, r), dt)
+    lrd.linear_fwd_act(X_, V_, U_, None, Z1, A1, H1, lrd.ACT_GELU, ws)
+    lrd.linear_fwd(X_, V_, U_, None, Z2, H2, ws)
+    lrd.gelu_fwd(Z2, A2)
+    g1, g2, tmp = empty((T, n_in), dt), empty((T, n_in), dt), empty((T, n_in), dt)
+    dU1, dU2, dV1, dV2 = f32((n_out, r)), f32((n_out, r)), f32((r, n_in)), f32((r, n_in))
+    lrd.linear_bwd_act(dY_, X_, H1, V_, U_, g1, dV1, dU1, None, 0, Zin_, lrd.ACT_GELU, ws)
+    lrd.linear_bwd(dY_, X_, H2, V_, U_, tmp, dV2, dU2, None, 0, ws)
+    lrd.gelu_bwd(tmp, Zin_, g2)
+    torch.cuda.synchronize()
+    assert torch.equal(Z1, Z2) and torch.equal(A1, A2) and torch.equal(g1, g2)
+    assert torch.equal(dU1, dU2) and torch.equal(dV1, dV2)
+    Ho, Zo = oracle.linear_fwd(seen(X, dt), seen(V, dt), seen(U, dt))
+    check(host(A1), oracle.gelu_fwd(Zo), dt, "act(Z)")
+    go = oracle.linear_bwd(seen(dY, dt), seen(X, dt), Ho, seen(V, dt), seen(U, dt), 0)
+    check(host(g1), oracle.gelu_bwd(go["dX"], seen(Zin, dt)), dt, "dZ_in")
 
 
 def test_errors_reported_by_status():
