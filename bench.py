@@ -28,6 +28,9 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 T_TOKENS, D_MODEL, D_FF, N_BLOCKS = 8192, 768, 3072, 12
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+# HBM bytes per launch of the reported kernel from rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000
+# (profiles/gemm2_ffn_stack_hbm_traffic.md).  Set to None whenever that kernel or its tiling changes.
+GEMM2_64_FWD_DOWN_TRAFFIC_BYTES = 40.6e6
 
 
 def layer_flops(T, n_in, n_out, r, mask, want_dx=True):
@@ -320,7 +323,8 @@ def main():
     k_bytes = sum(2 * (T_TOKENS * n_in + rank * n_in + T_TOKENS * rank) for n_in in (D_MODEL, D_FF)) / 2
     achieved = k_bytes / (k_us * 1e-6) / 1e9
     roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved / HBM_PEAK_GBS,
-                    traffic=None, kernel="gemm2_kernel<64,64,2,2,2,false,false,bf16> as H = X.V^T (lrd_linear_fwd)",
+                    traffic=GEMM2_64_FWD_DOWN_TRAFFIC_BYTES,
+                    kernel="gemm2_kernel<64,64,2,2,2,false,false,bf16> as H = X.V^T (lrd_linear_fwd)",
                     avg_us=k_us, launches=len(probe), bytes_per_launch=k_bytes)
 
     out = dict(metric="decomposed-layer fwd+bwd throughput (12-block encoder FFN stack)", value=tflops,
