@@ -40,7 +40,7 @@ struct KcTile {
     int kc8[CH];
     u32x4 st[DEPTH][CH];
 
-    __device__ __forceinline__ void init(const Operand& o, int row0, int tid)
+    __device__ __forceinline__ void init(const Operand& o, int row0, int tid, const ConvShape&)
     {
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
@@ -86,7 +86,7 @@ struct KmTile {
     int64_t ld;
     u32x4 st[DEPTH][CH];
 
-    __device__ __forceinline__ void init(const Operand& o, int col0, int tid)
+    __device__ __forceinline__ void init(const Operand& o, int col0, int tid, const ConvShape&)
     {
         ld = o.ld;
 #pragma unroll
@@ -118,12 +118,168 @@ struct KmTile {
     }
 };
 
-template <int ROWS, int NT, int DEPTH, bool KM>
-struct Tile;
+// ---- implicit-GEMM operands of a k x k convolution on NHWC data ---------------------------------
+// Same LDS layouts and the same clamp-the-address / zero-at-store rule as the plain tiles; only
+// the address of a 16-byte chunk comes from the tap geometry.  Channel counts are multiples of 8
+// on this path, so a chunk never straddles two taps.
+
+// A operand, k-contiguous.  FWD:   row = output pixel, k = (u, v, i), reads X[n, y*s+u-p, x*s+v-p, i].
+//                           DGRAD: row = input pixel,  k = (u, v, o), reads dY[n, (a+p-u)/s, (b+p-v)/s, o].
+template <int ROWS, int NT, int DEPTH, bool DGRAD>
+struct ConvRowsTile {
+    static constexpr int CH = (ROWS * 8 + NT - 1) / NT;
+    static constexpr bool FULL = (ROWS * 8) % NT == 0;
+    const bf16_t* base;
+    ConvShape cs;
+    int img[CH], py[CH], px[CH], kc8[CH];
+    bool rowok[CH];
+    bool ok[DEPTH][CH];
+    u32x4 st[DEPTH][CH];
+
+    __device__ __forceinline__ void init(const Operand& o, int row0, int tid, const ConvShape& shape)
+    {
+        base = o.p;
+        cs = shape;
+        const int gw = DGRAD ? cs.W : cs.Wo, gh = DGRAD ? cs.H : cs.Ho;
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            int c = tid + i * NT;
+            int row = row0 + (c >> 3);
+            rowok[i] = row < o.rows;
+            row = min(row, o.rows - 1);
+            kc8[i] = (c & 7) * 8;
+            px[i] = row % gw;
+            int q = row / gw;
+            py[i] = q % gh;
+            img[i] = q / gh;
+        }
+    }
+    __device__ __forceinline__ void load(int d, int k0, int kend, int tid)
+    {
+        const int ch = DGRAD ? cs.O : cs.I;            // channels of the tensor being gathered
+        const int sh = DGRAD ? cs.Ho : cs.H, sw = DGRAD ? cs.Wo : cs.W;
+#pragma unroll
+        for (int i = 0; i < CH; ++i)
+            if (FULL || tid + i * NT < ROWS * 8) {
+                int k = min(k0 + kc8[i], kend - 8);
+                int tap = k / ch, c0 = k - tap * ch;
+                int u = tap / cs.k, v = tap - u * cs.k;
+                int yy, xx;
+                bool inside;
+                if (DGRAD) {
+                    int ys = py[i] + cs.pad - u, xs = px[i] + cs.pad - v;
+                    yy = ys / cs.stride;
+                    xx = xs / cs.stride;
+                    inside = ys >= 0 && xs >= 0 && yy * cs.stride == ys && xx * cs.stride == xs && yy < sh && xx < sw;
+                } else {
+                    yy = py[i] * cs.stride + u - cs.pad;
+                    xx = px[i] * cs.stride + v - cs.pad;
+                    inside = yy >= 0 && xx >= 0 && yy < sh && xx < sw;
+                }
+                ok[d][i] = inside && rowok[i] && k0 + kc8[i] < kend;
+                yy = min(max(yy, 0), sh - 1);
+                xx = min(max(xx, 0), sw - 1);
+                st[d][i] = *reinterpret_cast<const u32x4*>(base + ((int64_t)(img[i] * sh + yy) * sw + xx) * ch + c0);
+            }
+    }
+    __device__ __forceinline__ void store(int d, bf16_t* lds, int, int, int tid) const
+    {
+        const u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            int c = tid + i * NT;
+            if (FULL || c < ROWS * 8)
+                *reinterpret_cast<u32x4*>(lds + (c >> 3) * LDK + (c & 7) * 8) = ok[d][i] ? st[d][i] : z;
+        }
+    }
+};
+
+// B operand, k-major.  DGRAD: column = input channel i, k = (u, v, o), reads W[o][u][v][i].
+//                      WGRAD: column = (u, v, i),        k = output pixel, reads X[n, y*s+u-p, x*s+v-p, i].
+template <int COLS, int NT, int DEPTH, bool WGRAD>
+struct ConvKmTile {
+    static constexpr int CPK = COLS / 8;
+    static constexpr int LDM = COLS + 16;
+    static constexpr int CH = (BK * CPK + NT - 1) / NT;
+    static constexpr bool FULL = (BK * CPK) % NT == 0;
+    const bf16_t* base;
+    ConvShape cs;
+    int krow[CH], c0[CH], tu[CH], tv[CH];
+    bool colok[CH];
+    bool ok[DEPTH][CH];
+    u32x4 st[DEPTH][CH];
+
+    __device__ __forceinline__ void init(const Operand& o, int col0, int tid, const ConvShape& shape)
+    {
+        base = o.p;
+        cs = shape;
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            int c = tid + i * NT;
+            int col = col0 + (c % CPK) * 8;
+            colok[i] = col < o.rows;
+            col = min(col, o.rows - 8);
+            krow[i] = c / CPK;
+            if (WGRAD) {
+                int tap = col / cs.I;
+                c0[i] = col - tap * cs.I;
+                tu[i] = tap / cs.k;
+                tv[i] = tap - tu[i] * cs.k;
+            } else {
+                c0[i] = col;
+                tu[i] = tv[i] = 0;
+            }
+        }
+    }
+    __device__ __forceinline__ void load(int d, int k0, int kend, int tid)
+    {
+#pragma unroll
+        for (int i = 0; i < CH; ++i)
+            if (FULL || tid + i * NT < BK * CPK) {
+                int k = min(k0 + krow[i], kend - 1);
+                bool inside = true;
+                int64_t off;
+                if (WGRAD) {
+                    int x = k % cs.Wo, q = k / cs.Wo;
+                    int y = q % cs.Ho, n = q / cs.Ho;
+                    int yy = y * cs.stride + tu[i] - cs.pad, xx = x * cs.stride + tv[i] - cs.pad;
+                    inside = yy >= 0 && xx >= 0 && yy < cs.H && xx < cs.W;
+                    yy = min(max(yy, 0), cs.H - 1);
+                    xx = min(max(xx, 0), cs.W - 1);
+                    off = ((int64_t)(n * cs.H + yy) * cs.W + xx) * cs.I + c0[i];
+                } else {
+                    int tap = k / cs.O, o = k - tap * cs.O;
+                    off = ((int64_t)o * cs.k * cs.k + tap) * cs.I + c0[i];
+                }
+                ok[d][i] = inside && colok[i] && k0 + krow[i] < kend;
+                st[d][i] = *reinterpret_cast<const u32x4*>(base + off);
+            }
+    }
+    __device__ __forceinline__ void store(int d, bf16_t* lds, int, int, int tid) const
+    {
+        const u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            int c = tid + i * NT;
+            if (FULL || c < BK * CPK)
+                *reinterpret_cast<u32x4*>(lds + (c / CPK) * LDM + (c % CPK) * 8) = ok[d][i] ? st[d][i] : z;
+        }
+    }
+};
+
+// Tile type by layout (k-major or not) and gather mode (GATHER_* of the product).
+template <int ROWS, int NT, int DEPTH, bool KM, int G, bool IS_A>
+struct TileSel { typedef KcTile<ROWS, NT, DEPTH> type; };
+template <int ROWS, int NT, int DEPTH, int G, bool IS_A>
+struct TileSel<ROWS, NT, DEPTH, true, G, IS_A> { typedef KmTile<ROWS, NT, DEPTH> type; };
 template <int ROWS, int NT, int DEPTH>
-struct Tile<ROWS, NT, DEPTH, false> : KcTile<ROWS, NT, DEPTH> {};
+struct TileSel<ROWS, NT, DEPTH, false, GATHER_CONV_FWD, true> { typedef ConvRowsTile<ROWS, NT, DEPTH, false> type; };
 template <int ROWS, int NT, int DEPTH>
-struct Tile<ROWS, NT, DEPTH, true> : KmTile<ROWS, NT, DEPTH> {};
+struct TileSel<ROWS, NT, DEPTH, false, GATHER_CONV_DGRAD, true> { typedef ConvRowsTile<ROWS, NT, DEPTH, true> type; };
+template <int ROWS, int NT, int DEPTH>
+struct TileSel<ROWS, NT, DEPTH, true, GATHER_CONV_DGRAD, false> { typedef ConvKmTile<ROWS, NT, DEPTH, false> type; };
+template <int ROWS, int NT, int DEPTH>
+struct TileSel<ROWS, NT, DEPTH, true, GATHER_CONV_WGRAD, false> { typedef ConvKmTile<ROWS, NT, DEPTH, true> type; };
 
 // Operand fragment of one 32-row block for one 16-wide k step, in the register layout of
 // v_mfma_f32_32x32x16_bf16: lane L holds row (L & 31), k = 8 * (L >> 5) + 0..7.
@@ -182,8 +338,8 @@ constexpr int gemm2_lds_bytes()
     return main > epi ? main : epi;
 }
 
-template <int BM, int BN, int WGM, int WGN, int DEPTH, bool A_KM, bool B_KM, class OutT>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm2_kernel(Operand A, Operand B, OutT* __restrict__ C, int64_t ldc,
+template <int BM, int BN, int WGM, int WGN, int DEPTH, bool A_KM, bool B_KM, class OutT, int G>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm2_kernel(Operand A, Operand B, ConvShape cs, OutT* __restrict__ C, int64_t ldc,
                                                                const float* __restrict__ bias, float* __restrict__ partial,
                                                                int M, int N, int K, int k_per_split, int epilogue,
                                                                bf16_t* __restrict__ aux, int64_t ldaux)
@@ -210,10 +366,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm2_kernel(Operand A, Operan
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    Tile<BM, NT, DEPTH, A_KM> ta;
-    Tile<BN, NT, DEPTH, B_KM> tb;
-    ta.init(A, m0, tid);
-    tb.init(B, n0, tid);
+    typename TileSel<BM, NT, DEPTH, A_KM, G, true>::type ta;
+    typename TileSel<BN, NT, DEPTH, B_KM, G, false>::type tb;
+    ta.init(A, m0, tid, cs);
+    tb.init(B, n0, tid, cs);
 
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
@@ -326,12 +482,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm2_kernel(Operand A, Operan
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int DEPTH, bool A_KM, bool B_KM, class OutT>
+template <int BM, int BN, int WGM, int WGN, int DEPTH, bool A_KM, bool B_KM, class OutT, int G = GATHER_NONE>
 hipError_t launch(const MatOp& op, const Operand& A, const Operand& B, hipStream_t st)
 {
     constexpr int NT = 64 * WGM * WGN;
     constexpr int lds_bytes = gemm2_lds_bytes<BM, BN, A_KM, B_KM, OutT>();
-    auto kern = gemm2_kernel<BM, BN, WGM, WGN, DEPTH, A_KM, B_KM, OutT>;
+    auto kern = gemm2_kernel<BM, BN, WGM, WGN, DEPTH, A_KM, B_KM, OutT, G>;
     static bool lds_allowed = false;
     if (!lds_allowed) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -344,7 +500,7 @@ hipError_t launch(const MatOp& op, const Operand& A, const Operand& B, hipStream
     splits = (int)ceil_div(op.K, kps);
     float* partial = splits > 1 ? op.partial : nullptr;
     dim3 grid((unsigned)ceil_div(op.M, BM), (unsigned)ceil_div(op.N, BN), (unsigned)splits);
-    hipLaunchKernelGGL(kern, grid, dim3(NT), lds_bytes, st, A, B, (OutT*)op.C, op.ldc, op.bias, partial, (int)op.M,
+    hipLaunchKernelGGL(kern, grid, dim3(NT), lds_bytes, st, A, B, op.cs, (OutT*)op.C, op.ldc, op.bias, partial, (int)op.M,
                        (int)op.N, (int)op.K, kps, op.epilogue, (bf16_t*)op.aux, op.ldaux);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -355,32 +511,51 @@ hipError_t launch(const MatOp& op, const Operand& A, const Operand& B, hipStream
 inline bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Tile choice: the largest tile that still yields about one workgroup per compute unit.
-template <bool A_KM, bool B_KM, class OutT>
+template <bool A_KM, bool B_KM, class OutT, int G = GATHER_NONE>
 hipError_t by_tile(const MatOp& op, const Operand& A, const Operand& B, hipStream_t st)
 {
     const int64_t splits = (op.splits > 1 && op.partial) ? op.splits : 1;
     auto wgs = [&](int bm, int bn) { return ceil_div(op.M, bm) * ceil_div(op.N, bn) * splits; };
-    if constexpr (sizeof(OutT) == 2 && !A_KM && !B_KM) {
+    if constexpr (sizeof(OutT) == 2 && !A_KM && !B_KM && G == GATHER_NONE) {
         if (op.K >= 1024 && wgs(256, 256) >= 224) return launch<256, 256, 2, 4, 2, false, false, OutT>(op, A, B, st);
     }
     if (wgs(128, 128) >= 200 || (op.M > 64 && op.N > 64 && wgs(64, 64) > 2048))
-        return launch<128, 128, 2, 2, 2, A_KM, B_KM, OutT>(op, A, B, st);
-    return launch<64, 64, 2, 2, 2, A_KM, B_KM, OutT>(op, A, B, st);
+        return launch<128, 128, 2, 2, 2, A_KM, B_KM, OutT, G>(op, A, B, st);
+    return launch<64, 64, 2, 2, 2, A_KM, B_KM, OutT, G>(op, A, B, st);
 }
 
 }  // namespace
 
 bool mfma_gemm2_supported(const MatOp& op)
 {
-    if (!op.in_bf16 || op.gather != GATHER_NONE) return false;
+    if (!op.in_bf16) return false;
     if (op.M < 1 || op.N < 1 || op.K < 8) return false;
     if (op.M >= (int64_t(1) << 31) || op.N >= (int64_t(1) << 31) || op.K >= (int64_t(1) << 31)) return false;
-    if (!al16(op.A) || !al16(op.B) || !al16(op.C) || op.K % 8 != 0) return false;
-    const bool akm = op.a_sk != 1, bkm = op.b_sk != 1;
-    if (akm && (op.a_sm != 1 || op.a_sk % 8 != 0 || op.M % 8 != 0)) return false;
-    if (!akm && op.a_sm % 8 != 0) return false;
-    if (bkm && (op.b_sn != 1 || op.b_sk % 8 != 0 || op.N % 8 != 0)) return false;
-    if (!bkm && op.b_sn % 8 != 0) return false;
+    if (!al16(op.A) || !al16(op.B) || !al16(op.C)) return false;
+    bool akm, bkm;
+    if (op.gather == GATHER_NONE) {
+        akm = op.a_sk != 1;
+        bkm = op.b_sk != 1;
+        if (akm && (op.a_sm != 1 || op.a_sk % 8 != 0 || op.M % 8 != 0)) return false;
+        if (!akm && op.a_sm % 8 != 0) return false;
+        if (bkm && (op.b_sn != 1 || op.b_sk % 8 != 0 || op.N % 8 != 0)) return false;
+        if (!bkm && op.b_sn % 8 != 0) return false;
+    } else {
+        // implicit-GEMM convolution: channel counts must keep every 16-byte chunk inside one tap
+        if (op.cs.I % 8 != 0 || op.cs.O % 8 != 0 || op.cs.k < 1 || op.cs.stride < 1) return false;
+        if ((int64_t)op.cs.N * op.cs.H * op.cs.W * op.cs.I >= (int64_t(1) << 31)) return false;
+        if ((int64_t)op.cs.N * op.cs.Ho * op.cs.Wo * op.cs.O >= (int64_t(1) << 31)) return false;
+        if (op.gather == GATHER_CONV_FWD) {
+            akm = false; bkm = false;
+            if (op.b_sk != 1 || op.b_sn % 8 != 0) return false;
+        } else if (op.gather == GATHER_CONV_DGRAD) {
+            akm = false; bkm = true;
+        } else {
+            akm = true; bkm = true;
+            if (op.a_sm != 1 || op.a_sk % 8 != 0 || op.M % 8 != 0) return false;
+        }
+    }
+    if ((!akm || !bkm) && op.K % 8 != 0) return false;    // a k-contiguous operand is read in chunks of 8 k
     if (akm && !bkm) return false;                       // layout not used by any layer pass
     if (op.out_f32) {
         if (!(akm && bkm)) return false;                 // fp32 results are weight gradients
@@ -397,6 +572,21 @@ bool mfma_gemm2_supported(const MatOp& op)
 
 hipError_t mfma_gemm2(const MatOp& op, hipStream_t st)
 {
+    if (op.gather == GATHER_CONV_FWD) {
+        Operand A{(const bf16_t*)op.A, 0, (int)op.M};
+        Operand B{(const bf16_t*)op.B, op.b_sn, (int)op.N};
+        return by_tile<false, false, bf16_t, GATHER_CONV_FWD>(op, A, B, st);
+    }
+    if (op.gather == GATHER_CONV_DGRAD) {
+        Operand A{(const bf16_t*)op.A, 0, (int)op.M};
+        Operand B{(const bf16_t*)op.B, 0, (int)op.N};
+        return by_tile<false, true, bf16_t, GATHER_CONV_DGRAD>(op, A, B, st);
+    }
+    if (op.gather == GATHER_CONV_WGRAD) {
+        Operand A{(const bf16_t*)op.A, op.a_sk, (int)op.M};
+        Operand B{(const bf16_t*)op.B, 0, (int)op.N};
+        return by_tile<true, true, float, GATHER_CONV_WGRAD>(op, A, B, st);
+    }
     const bool akm = op.a_sk != 1, bkm = op.b_sk != 1;
     Operand A{(const bf16_t*)op.A, akm ? op.a_sk : op.a_sm, (int)op.M};
     Operand B{(const bf16_t*)op.B, bkm ? op.b_sk : op.b_sn, (int)op.N};
