@@ -211,6 +211,56 @@ def cpu_baseline(np, si, oracle, rank):
                 tokens_per_s=T / (dt * N_BLOCKS / blocks))
 
 
+def rank_sweep(args, torch, lrd):
+    """Config 3: one 4096 x 4096 linear, 16384 tokens, bf16; forward + backward time against the rank
+    (raw ranks and their quantized neighbours) with nothing / V / U frozen, beside the dense layer.
+    Timing only (parity of these shapes is covered by the tests); prints one JSON line."""
+    T, d = 16384, 4096
+    bf = torch.bfloat16
+    gen = torch.Generator(device="cuda").manual_seed(230903824 + 3)
+
+    def rnd(*shape, scale=1.0):
+        return (torch.randn(*shape, device="cuda", generator=gen) * scale).to(bf)
+
+    def timeit(fn, iters):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        for _ in range(iters):
+            fn()
+        e.record()
+        torch.cuda.synchronize()
+        return s.elapsed_time(e) * 1e3 / iters
+
+    X, dY = rnd(T, d), rnd(T, d)
+    Y, dX = torch.empty(T, d, dtype=bf, device="cuda"), torch.empty(T, d, dtype=bf, device="cuda")
+    ranks = sorted(set(list(range(args.sweep_step, 1025, args.sweep_step)) +
+                       [q + o for q in range(64, 1025, 64) for o in (-1, 0, 1) if 1 <= q + o <= 1024] + [1]))
+    ws = torch.empty(max(lrd.linear_workspace_bytes(T, d, d, r, lrd.BF16, 0) for r in ranks) + 256,
+                     dtype=torch.uint8, device="cuda")
+    points = []
+    for r in ranks:
+        V, U = rnd(r, d, scale=d ** -0.5), rnd(d, r, scale=r ** -0.5)
+        H = torch.empty(T, r, dtype=bf, device="cuda")
+        dV, dU = torch.empty(r, d, device="cuda"), torch.empty(d, r, device="cuda")
+        fwd = timeit(lambda: lrd.linear_fwd(X, V, U, None, Y, H, ws), args.sweep_iters)
+        row = dict(r=r, fwd_us=fwd)
+        for name, mask in (("none", 0), ("V", 1), ("U", 2)):
+            row[f"bwd_us_frozen_{name}"] = timeit(
+                lambda: lrd.linear_bwd(dY, X, H, V, U, dX, dV, dU, None, mask, ws), args.sweep_iters)
+        row["tflops_fwd_bwd_V_frozen"] = 10.0 * T * d * r / ((fwd + row["bwd_us_frozen_V"]) * 1e-6) / 1e12
+        points.append(row)
+    W, dW = rnd(d, d, scale=d ** -0.5), torch.empty(d, d, device="cuda")
+    wsd = torch.empty(lrd.dense_linear_workspace_bytes(T, d, d, lrd.BF16) + 256, dtype=torch.uint8, device="cuda")
+    dense_f = timeit(lambda: lrd.dense_linear_fwd(X, W, None, Y, wsd), 5)
+    dense_b = timeit(lambda: lrd.dense_linear_bwd(dY, X, W, dX, dW, wsd), 5)
+    print(json.dumps(dict(metric="rank sweep: decomposed 4096x4096 linear, 16384 tokens, bf16 (fwd / bwd microseconds)",
+                          dense=dict(fwd_us=dense_f, bwd_us=dense_b, tflops=6.0 * T * d * d / ((dense_f + dense_b) * 1e-6) / 1e12),
+                          points=points)))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -219,6 +269,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-comparators", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
+    ap.add_argument("--rank-sweep", action="store_true", help="run the rank sweep (config 3) instead of the FFN stack")
+    ap.add_argument("--sweep-step", type=int, default=16)
+    ap.add_argument("--sweep-iters", type=int, default=5)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 256 MiB device copies (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -237,6 +290,10 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+
+    if args.rank_sweep:
+        rank_sweep(args, torch, lrd)
+        return
 
     if args.calibrate_copy:
         src = torch.ones(1 << 27, dtype=torch.bfloat16, device="cuda")

@@ -84,6 +84,21 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
     }
 }
 
+// dst[i][j] (rows_d x cols_d, leading dimension ldd) = src[i][j] where it exists (i < rows_s, j < cols_s), else 0.
+template <class T>
+__global__ __launch_bounds__(256) void copy2d_kernel(const T* __restrict__ src, int64_t lds_, int64_t rows_s, int64_t cols_s,
+                                                     T* __restrict__ dst, int64_t ldd, int64_t rows_d, int64_t cols_d)
+{
+    const int64_t total = rows_d * cols_d;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += stride) {
+        int64_t i = e / cols_d, j = e - i * cols_d;
+        T v = (T)0.f;
+        if (i < rows_s && j < cols_s) v = src[i * lds_ + j];
+        dst[i * ldd + j] = v;
+    }
+}
+
 inline unsigned blocks_for(int64_t items)
 {
     int64_t b = ceil_div(items, 256);
@@ -116,6 +131,20 @@ hipError_t column_sums(const void* dY, float* out, int64_t T, int64_t n, bool bf
     dim3 grid((unsigned)ceil_div(n, 64));
     if (bf16) hipLaunchKernelGGL(column_sums_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)dY, out, T, n);
     else hipLaunchKernelGGL(column_sums_kernel<float>, grid, dim3(256), 0, st, (const float*)dY, out, T, n);
+    return hipGetLastError();
+}
+
+hipError_t copy2d(const void* src, int64_t ld_src, int64_t rows_src, int64_t cols_src, void* dst, int64_t ld_dst,
+                  int64_t rows_dst, int64_t cols_dst, int elem_bytes, hipStream_t st)
+{
+    if (rows_dst <= 0 || cols_dst <= 0) return hipSuccess;
+    dim3 grid(blocks_for(rows_dst * cols_dst));
+    if (elem_bytes == 2)
+        hipLaunchKernelGGL(copy2d_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)src, ld_src, rows_src, cols_src,
+                           (bf16_t*)dst, ld_dst, rows_dst, cols_dst);
+    else
+        hipLaunchKernelGGL(copy2d_kernel<float>, grid, dim3(256), 0, st, (const float*)src, ld_src, rows_src, cols_src,
+                           (float*)dst, ld_dst, rows_dst, cols_dst);
     return hipGetLastError();
 }
 

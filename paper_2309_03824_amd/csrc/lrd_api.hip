@@ -32,6 +32,16 @@ hipError_t run_chain(const ChainOp& ch, hipStream_t st)
     return e;
 }
 
+// A bf16 rank that is not a multiple of 8 breaks 16-byte loads on every operand whose leading
+// dimension is r.  Such a pair is evaluated at the padded rank r8 = ceil(r/8)*8 on zero-padded
+// copies of the (small) factors and of H, so that the large activations keep the fast kernels;
+// the rank then costs the padding copies and the padded MFMA work, not a different code path.
+inline int64_t pad8(int64_t r) { return (r + 7) / 8 * 8; }
+inline bool pads_rank(int64_t in, int64_t out, int64_t r, lrd_dtype dt)
+{
+    return dt == LRD_BF16 && r % 8 != 0 && in % 8 == 0 && out % 8 == 0;
+}
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round256(size_t b) { return (b + 255) & ~size_t(255); }
 inline size_t esize(lrd_dtype dt) { return dt == LRD_BF16 ? 2 : 4; }
@@ -164,6 +174,12 @@ size_t lrd_linear_workspace_bytes(int64_t T, int64_t in, int64_t out, int64_t r,
 {
     (void)freeze_mask;
     if (!dtype_ok(dt) || !linear_dims_ok(T, in, out, r)) return 0;
+    if (pads_rank(in, out, r, dt)) {
+        const size_t r8 = (size_t)pad8(r);
+        size_t pads = round256((size_t)out * r8 * 2) + round256(r8 * (size_t)in * 2) + round256((size_t)T * r8 * 2) +
+                      round256((size_t)out * r8 * 4) + round256(r8 * (size_t)in * 4);
+        return pads + lrd_linear_workspace_bytes(T, in, out, (int64_t)r8, dt, freeze_mask);
+    }
     size_t act = round256((size_t)T * (size_t)r * esize(dt));
     // forward: H when not side-stored; backward: dH, a recomputed H, and split-K partials
     size_t bwd = 2 * act + partial_bytes(out, r, T, dt) + partial_bytes(r, in, T, dt);
@@ -189,6 +205,22 @@ lrd_status lrd_linear_fwd_act(const void* X, const void* V, const void* U, const
         !aligned16(bias) || !aligned16(Y_act))
         return LRD_ERR_ALIGNMENT;
     hipStream_t st = (hipStream_t)hip_stream;
+
+    if (pads_rank(in, out, r, dt)) {
+        const int64_t r8 = pad8(r);
+        Carver cv(ws, ws_bytes);
+        void* Up = cv.take((size_t)out * r8 * 2);
+        void* Vp = cv.take((size_t)r8 * in * 2);
+        void* Hp = cv.take((size_t)T * r8 * 2);
+        if (!cv.ok) return LRD_ERR_WORKSPACE;
+        LRD_TRY(copy2d(U, r, out, r, Up, r8, out, r8, 2, st));
+        LRD_TRY(copy2d(V, in, r, in, Vp, in, r8, in, 2, st));
+        lrd_status rc = lrd_linear_fwd_act(X, Vp, Up, bias, Y, Y_act, Hp, act, T, in, out, r8, dt, (char*)ws + cv.used,
+                                           ws_bytes - cv.used, hip_stream);
+        if (rc != LRD_OK) return rc;
+        if (H_save) LRD_TRY(copy2d(Hp, r8, T, r, H_save, r, T, r, 2, st));
+        return LRD_OK;
+    }
 
     if (dt == LRD_BF16) {
         ChainOp ch;
@@ -250,6 +282,26 @@ lrd_status lrd_linear_bwd_act(const void* dY, const void* X, const void* H, cons
         !aligned16(ws) || (train_v && !aligned16(dV)) || (train_u && !aligned16(dU)) || !aligned16(dbias))
         return LRD_ERR_ALIGNMENT;
     hipStream_t st = (hipStream_t)hip_stream;
+    if (pads_rank(in, out, r, dt)) {
+        const int64_t r8 = pad8(r);
+        Carver cvp(ws, ws_bytes);
+        void* Up = cvp.take((size_t)out * r8 * 2);
+        void* Vp = cvp.take((size_t)r8 * in * 2);
+        void* Hp = cvp.take((size_t)T * r8 * 2);
+        float* dUp = (float*)cvp.take((size_t)out * r8 * 4);
+        float* dVp = (float*)cvp.take((size_t)r8 * in * 4);
+        if (!cvp.ok) return LRD_ERR_WORKSPACE;
+        LRD_TRY(copy2d(U, r, out, r, Up, r8, out, r8, 2, st));
+        LRD_TRY(copy2d(V, in, r, in, Vp, in, r8, in, 2, st));
+        const bool have_h = H && train_u;
+        if (have_h) LRD_TRY(copy2d(H, r, T, r, Hp, r8, T, r8, 2, st));
+        lrd_status rc = lrd_linear_bwd_act(dY, X, have_h ? Hp : nullptr, Vp, Up, dX, dVp, dUp, dbias, freeze_mask, Z_in, act, T,
+                                           in, out, r8, dt, (char*)ws + cvp.used, ws_bytes - cvp.used, hip_stream);
+        if (rc != LRD_OK) return rc;
+        if (train_u) LRD_TRY(copy2d(dUp, r8, out, r, dU, r, out, r, 4, st));
+        if (train_v) LRD_TRY(copy2d(dVp, in, r, in, dV, in, r, in, 4, st));
+        return LRD_OK;
+    }
     Carver cv(ws, ws_bytes);
     const size_t act_bytes = (size_t)T * r * esize(dt);
     const bool need_dH = dX || train_v;

@@ -80,6 +80,9 @@ bool probe_take(int role, hipEvent_t* start, hipEvent_t* stop);
 hipError_t gelu_fwd(const void* Z, void* A, int64_t n, bool bf16, hipStream_t st);
 hipError_t gelu_bwd(const void* dA, const void* Z, void* dZ, int64_t n, bool bf16, hipStream_t st);
 hipError_t column_sums(const void* dY, float* out, int64_t T, int64_t n, bool bf16, hipStream_t st);
+// Zero-padding / cropping copy of a row-major matrix (elem_bytes 2 or 4).
+hipError_t copy2d(const void* src, int64_t ld_src, int64_t rows_src, int64_t cols_src, void* dst, int64_t ld_dst,
+                  int64_t rows_dst, int64_t cols_dst, int elem_bytes, hipStream_t st);
 hipError_t reduce_partials(const float* partial, float* C, int64_t ldc, int64_t M, int64_t N,
                            int splits, hipStream_t st);
 
