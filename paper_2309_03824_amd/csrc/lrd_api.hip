@@ -413,10 +413,47 @@ lrd_status lrd_dense_linear_bwd(const void* dY, const void* X, const void* W, vo
 }
 
 // ------------------------------------------------------------------------------------ Tucker conv
+// Same rule for the Tucker triple: ranks that are not multiples of 8 run at the padded ranks on
+// zero-padded copies of P1, G, P2 (and of saved A / B in the backward).
+inline bool pads_tucker(const lrd_conv_geom& g, lrd_dtype dt)
+{
+    return dt == LRD_BF16 && (g.r1 % 8 != 0 || g.r2 % 8 != 0) && g.C % 8 == 0 && g.S % 8 == 0;
+}
+
+struct TuckerPads {
+    lrd_conv_geom gp;
+    size_t p1, gc, p2, a, b, dp1, dg, dp2;   // byte sizes of the padded copies
+    size_t total() const { return p1 + gc + p2 + a + b + dp1 + dg + dp2; }
+};
+
+inline TuckerPads tucker_pads(const lrd_conv_geom& g)
+{
+    TuckerPads t;
+    t.gp = g;
+    t.gp.r1 = pad8(g.r1);
+    t.gp.r2 = pad8(g.r2);
+    ConvShape cs = core_shape(g, g.r1, g.r2);
+    const size_t kk = (size_t)g.k * g.k, pin = (size_t)g.N * g.H * g.W, pout = (size_t)g.N * cs.Ho * cs.Wo;
+    const size_t r1 = t.gp.r1, r2 = t.gp.r2;
+    t.p1 = round256(r1 * g.C * 2);
+    t.gc = round256(r2 * kk * r1 * 2);
+    t.p2 = round256((size_t)g.S * r2 * 2);
+    t.a = round256(pin * r1 * 2);
+    t.b = round256(pout * r2 * 2);
+    t.dp1 = round256(r1 * g.C * 4);
+    t.dg = round256(r2 * kk * r1 * 4);
+    t.dp2 = round256((size_t)g.S * r2 * 4);
+    return t;
+}
+
 size_t lrd_tucker_conv_workspace_bytes(const lrd_conv_geom* g, lrd_dtype dt, uint32_t freeze_mask)
 {
     (void)freeze_mask;
     if (!dtype_ok(dt) || !geom_ok(g, true)) return 0;
+    if (pads_tucker(*g, dt)) {
+        TuckerPads t = tucker_pads(*g);
+        return t.total() + lrd_tucker_conv_workspace_bytes(&t.gp, dt, freeze_mask);
+    }
     ConvShape cs = core_shape(*g, g->r1, g->r2);
     size_t pin = (size_t)g->N * g->H * g->W, pout = (size_t)g->N * cs.Ho * cs.Wo;
     size_t a = round256(pin * g->r1 * esize(dt)), b = round256(pout * g->r2 * esize(dt));
@@ -439,6 +476,26 @@ lrd_status lrd_tucker_conv_fwd(const void* X, const void* P1, const void* G, con
     ConvShape cs = core_shape(*g, g->r1, g->r2);
     const int64_t pin = g->N * g->H * g->W, pout = g->N * (int64_t)cs.Ho * cs.Wo;
     const int64_t kk = (int64_t)g->k * g->k;
+    if (pads_tucker(*g, dt)) {
+        TuckerPads t = tucker_pads(*g);
+        const int64_t r1 = g->r1, r2 = g->r2, q1 = t.gp.r1, q2 = t.gp.r2;
+        Carver cp(ws, ws_bytes);
+        void* P1p = cp.take(t.p1);
+        void* Gp = cp.take(t.gc);
+        void* P2p = cp.take(t.p2);
+        void* Ap = cp.take(t.a);
+        void* Bp = cp.take(t.b);
+        if (!cp.ok) return LRD_ERR_WORKSPACE;
+        LRD_TRY(copy2d(P1, g->C, r1, g->C, P1p, g->C, q1, g->C, 2, st));
+        LRD_TRY(copy2d(G, r1, r2 * kk, r1, Gp, q1, q2 * kk, q1, 2, st));
+        LRD_TRY(copy2d(P2, r2, g->S, r2, P2p, q2, g->S, q2, 2, st));
+        lrd_status rc = lrd_tucker_conv_fwd(X, P1p, Gp, P2p, Y, Ap, Bp, &t.gp, dt, (char*)ws + cp.used, ws_bytes - cp.used,
+                                            hip_stream);
+        if (rc != LRD_OK) return rc;
+        if (A_save) LRD_TRY(copy2d(Ap, q1, pin, r1, A_save, r1, pin, r1, 2, st));
+        if (B_save) LRD_TRY(copy2d(Bp, q2, pout, r2, B_save, r2, pout, r2, 2, st));
+        return LRD_OK;
+    }
     Carver cv(ws, ws_bytes);
     void* A = A_save ? A_save : cv.take((size_t)pin * g->r1 * esize(dt));
     void* B = B_save ? B_save : cv.take((size_t)pout * g->r2 * esize(dt));
@@ -475,6 +532,34 @@ lrd_status lrd_tucker_conv_bwd(const void* dY, const void* X, const void* A, con
     const int64_t pin = g->N * g->H * g->W, pout = g->N * (int64_t)cs.Ho * cs.Wo;
     const int64_t kk = (int64_t)g->k * g->k;
     const int64_t r1 = g->r1, r2 = g->r2, C = g->C, S = g->S;
+    if (pads_tucker(*g, dt)) {
+        TuckerPads t = tucker_pads(*g);
+        const int64_t q1 = t.gp.r1, q2 = t.gp.r2;
+        Carver cp(ws, ws_bytes);
+        void* P1p = cp.take(t.p1);
+        void* Gp = cp.take(t.gc);
+        void* P2p = cp.take(t.p2);
+        void* Ap = cp.take(t.a);
+        void* Bp = cp.take(t.b);
+        float* dP1p = (float*)cp.take(t.dp1);
+        float* dGp = (float*)cp.take(t.dg);
+        float* dP2p = (float*)cp.take(t.dp2);
+        if (!cp.ok) return LRD_ERR_WORKSPACE;
+        LRD_TRY(copy2d(P1, C, r1, C, P1p, C, q1, C, 2, st));
+        LRD_TRY(copy2d(G, r1, r2 * kk, r1, Gp, q1, q2 * kk, q1, 2, st));
+        LRD_TRY(copy2d(P2, r2, S, r2, P2p, q2, S, q2, 2, st));
+        const bool have_a = A && need_A, have_b = B && t2;
+        if (have_a) LRD_TRY(copy2d(A, r1, pin, r1, Ap, q1, pin, q1, 2, st));
+        if (have_b) LRD_TRY(copy2d(B, r2, pout, r2, Bp, q2, pout, q2, 2, st));
+        lrd_status rc = lrd_tucker_conv_bwd(dY, X, have_a ? Ap : nullptr, have_b ? Bp : nullptr, P1p, Gp, P2p, dX, dP1p, dGp,
+                                            dP2p, freeze_mask, &t.gp, dt, (char*)ws + cp.used, ws_bytes - cp.used,
+                                            hip_stream);
+        if (rc != LRD_OK) return rc;
+        if (t1) LRD_TRY(copy2d(dP1p, C, r1, C, dP1, C, r1, C, 4, st));
+        if (tg) LRD_TRY(copy2d(dGp, q1, r2 * kk, r1, dG, r1, r2 * kk, r1, 4, st));
+        if (t2) LRD_TRY(copy2d(dP2p, q2, S, r2, dP2, r2, S, r2, 4, st));
+        return LRD_OK;
+    }
     Carver cv(ws, ws_bytes);
     const bool need_dA = dX || t1;
     const bool need_dB = need_dA || tg;
