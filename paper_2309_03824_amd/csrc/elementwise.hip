@@ -72,15 +72,45 @@ __global__ __launch_bounds__(256) void column_sums_kernel(const T* __restrict__ 
     if (lane == 0 && col < n) out[col] = (part[0][c] + part[1][c]) + (part[2][c] + part[3][c]);
 }
 
-__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, float* __restrict__ C,
+// C[m][n] = sum_z partial[z][m][n], slices added in ascending z so the result does not depend on
+// scheduling.  VEC consecutive columns per thread (N and ldc are multiples of VEC); OutT is the
+// result type (fp32 weight gradients, or bf16 activations rounded once from the fp32 sum).
+template <int VEC, class OutT>
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, OutT* __restrict__ C,
                                                               int64_t ldc, int64_t M, int64_t N, int splits)
 {
-    int64_t total = M * N;
-    int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
-        float s = 0.f;
-        for (int z = 0; z < splits; ++z) s += partial[(int64_t)z * total + i];
-        C[(i / N) * ldc + (i % N)] = s;
+    const int64_t total = M * N;
+    const int64_t groups = total / VEC;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < groups; g += stride) {
+        const int64_t i = g * VEC;
+        float s[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) s[e] = 0.f;
+        for (int z = 0; z < splits; ++z) {
+            const float* p = partial + (int64_t)z * total + i;
+            if constexpr (VEC % 4 == 0) {
+#pragma unroll
+                for (int q = 0; q < VEC / 4; ++q) {
+                    f32x4 v = *reinterpret_cast<const f32x4*>(p + 4 * q);
+                    s[4 * q] += v.x; s[4 * q + 1] += v.y; s[4 * q + 2] += v.z; s[4 * q + 3] += v.w;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) s[e] += p[e];
+            }
+        }
+        OutT* out = C + (i / N) * ldc + (i % N);
+        if constexpr (VEC == 8 && sizeof(OutT) == 2) {
+            u32x4 pk = {pack_bf16(s[0], s[1]), pack_bf16(s[2], s[3]), pack_bf16(s[4], s[5]), pack_bf16(s[6], s[7])};
+            *reinterpret_cast<u32x4*>(out) = pk;
+        } else if constexpr (VEC == 4 && sizeof(OutT) == 4) {
+            f32x4 v = {s[0], s[1], s[2], s[3]};
+            *reinterpret_cast<f32x4*>(out) = v;
+        } else {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) out[e] = from_f32<OutT>(s[e]);
+        }
     }
 }
 
@@ -148,10 +178,26 @@ hipError_t copy2d(const void* src, int64_t ld_src, int64_t rows_src, int64_t col
     return hipGetLastError();
 }
 
-hipError_t reduce_partials(const float* partial, float* C, int64_t ldc, int64_t M, int64_t N, int splits,
+hipError_t reduce_partials(const float* partial, void* C, bool c_bf16, int64_t ldc, int64_t M, int64_t N, int splits,
                            hipStream_t st)
 {
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks_for(M * N)), dim3(256), 0, st, partial, C, ldc, M, N, splits);
+    if (M <= 0 || N <= 0) return hipSuccess;
+    const bool al = (reinterpret_cast<uintptr_t>(C) & 15u) == 0 && (reinterpret_cast<uintptr_t>(partial) & 15u) == 0;
+    if (c_bf16) {
+        if (al && N % 8 == 0 && ldc % 8 == 0)
+            hipLaunchKernelGGL((reduce_partials_kernel<8, bf16_t>), dim3(blocks_for(M * N / 8)), dim3(256), 0, st, partial,
+                               (bf16_t*)C, ldc, M, N, splits);
+        else
+            hipLaunchKernelGGL((reduce_partials_kernel<1, bf16_t>), dim3(blocks_for(M * N)), dim3(256), 0, st, partial,
+                               (bf16_t*)C, ldc, M, N, splits);
+    } else {
+        if (al && N % 4 == 0 && ldc % 4 == 0)
+            hipLaunchKernelGGL((reduce_partials_kernel<4, float>), dim3(blocks_for(M * N / 4)), dim3(256), 0, st, partial,
+                               (float*)C, ldc, M, N, splits);
+        else
+            hipLaunchKernelGGL((reduce_partials_kernel<1, float>), dim3(blocks_for(M * N)), dim3(256), 0, st, partial,
+                               (float*)C, ldc, M, N, splits);
+    }
     return hipGetLastError();
 }
 

@@ -108,6 +108,33 @@ size_t partial_bytes(int64_t M, int64_t N, int64_t K, lrd_dtype dt)
     return s > 1 ? round256((size_t)s * (size_t)M * (size_t)N * sizeof(float)) : 0;
 }
 
+// The same for a product whose result is a narrow activation.
+size_t act_partial_bytes(int64_t M, int64_t N, int64_t K, lrd_dtype dt)
+{
+    int s = choose_splits_act(M, N, K, dt == LRD_BF16);
+    return s > 1 ? round256((size_t)s * (size_t)M * (size_t)N * sizeof(float)) : 0;
+}
+
+// Split products of one linear pass run one after the other on the stream and share one region.
+size_t linear_partial_region(int64_t T, int64_t in, int64_t out, int64_t r, lrd_dtype dt, bool backward)
+{
+    const size_t h = act_partial_bytes(T, r, in, dt);   // H = X.V^T (forward, or recomputed in the backward)
+    if (!backward) return h;
+    return std::max(std::max(h, act_partial_bytes(T, r, out, dt)),
+                    std::max(partial_bytes(out, r, T, dt), partial_bytes(r, in, T, dt)));
+}
+
+enum SplitKind { SPLIT_WGRAD, SPLIT_ACT };
+void share_splits(MatOp& op, void* region, lrd_dtype dt, SplitKind kind)
+{
+    int s = kind == SPLIT_WGRAD ? choose_splits(op.M, op.N, op.K, dt == LRD_BF16)
+                                : choose_splits_act(op.M, op.N, op.K, dt == LRD_BF16);
+    if (s > 1 && region) {
+        op.partial = (float*)region;
+        op.splits = s;
+    }
+}
+
 void attach_splits(MatOp& op, Carver& cv, lrd_dtype dt)
 {
     int s = choose_splits(op.M, op.N, op.K, dt == LRD_BF16);
@@ -181,9 +208,10 @@ size_t lrd_linear_workspace_bytes(int64_t T, int64_t in, int64_t out, int64_t r,
         return pads + lrd_linear_workspace_bytes(T, in, out, (int64_t)r8, dt, freeze_mask);
     }
     size_t act = round256((size_t)T * (size_t)r * esize(dt));
-    // forward: H when not side-stored; backward: dH, a recomputed H, and split-K partials
-    size_t bwd = 2 * act + partial_bytes(out, r, T, dt) + partial_bytes(r, in, T, dt);
-    return std::max(act, bwd);
+    // forward: H when not side-stored; backward: dH and a recomputed H; both: one split-K region
+    size_t fwd = act + linear_partial_region(T, in, out, r, dt, false);
+    size_t bwd = 2 * act + linear_partial_region(T, in, out, r, dt, true);
+    return std::max(fwd, bwd);
 }
 
 lrd_status lrd_linear_fwd(const void* X, const void* V, const void* U, const float* bias, void* Y,
@@ -240,8 +268,11 @@ lrd_status lrd_linear_fwd_act(const void* X, const void* V, const void* U, const
     }
     Carver cv(ws, ws_bytes);
     void* H = H_save ? H_save : cv.take((size_t)T * r * esize(dt));
-    if (!H) return LRD_ERR_WORKSPACE;
+    const size_t region_bytes = linear_partial_region(T, in, out, r, dt, false);
+    void* region = region_bytes ? cv.take(region_bytes) : nullptr;
+    if (!H || !cv.ok) return LRD_ERR_WORKSPACE;
     MatOp g1 = nt(X, in, V, in, H, r, T, r, in, dt, false);
+    share_splits(g1, region, dt, SPLIT_ACT);
     MatOp g2 = nt(H, r, U, r, Y, out, T, out, r, dt, false);
     g2.bias = bias;
     g1.role = LRD_ROLE_FWD_DOWN;
@@ -309,24 +340,18 @@ lrd_status lrd_linear_bwd_act(const void* dY, const void* X, const void* H, cons
     // Carve everything first so that a short workspace is reported before any launch.
     void* dH = need_dH ? cv.take(act_bytes) : nullptr;
     void* Hre = (train_u && !H) ? cv.take(act_bytes) : nullptr;
+    const size_t region_bytes = linear_partial_region(T, in, out, r, dt, true);
+    void* region = region_bytes ? cv.take(region_bytes) : nullptr;
     MatOp wu, wv;
     if (train_u) {
         wu = tn(dY, out, H ? H : Hre, r, dU, r, out, r, T, dt);
         wu.role = LRD_ROLE_WGRAD_U;
-        attach_splits(wu, cv, dt);
+        share_splits(wu, region, dt, SPLIT_WGRAD);
     }
     if (train_v) {
         wv = tn(dH, r, X, in, dV, in, r, in, T, dt);
         wv.role = LRD_ROLE_WGRAD_V;
-        // the two weight-gradient products run one after the other and may share partials
-        if (train_u && wu.partial) {
-            int s = choose_splits(wv.M, wv.N, wv.K, dt == LRD_BF16);
-            size_t need = (size_t)s * wv.M * wv.N * sizeof(float), have = round256((size_t)wu.splits * wu.M * wu.N * sizeof(float));
-            if (s > 1 && need <= have) { wv.partial = wu.partial; wv.splits = s; }
-            else attach_splits(wv, cv, dt);
-        } else {
-            attach_splits(wv, cv, dt);
-        }
+        share_splits(wv, region, dt, SPLIT_WGRAD);
     }
     if (!cv.ok) return LRD_ERR_WORKSPACE;
 
@@ -350,6 +375,7 @@ lrd_status lrd_linear_bwd_act(const void* dY, const void* X, const void* H, cons
         if (!fused) {
             MatOp d1 = nn(dY, out, U, r, dH, r, T, r, out, dt);
             d1.role = LRD_ROLE_DGRAD_UP;
+            share_splits(d1, region, dt, SPLIT_ACT);
             LRD_TRY(run_matop(d1, st));
             if (dX) {
                 MatOp d2 = nn(dH, r, V, in, dX, in, T, in, r, dt);
@@ -364,7 +390,11 @@ lrd_status lrd_linear_bwd_act(const void* dY, const void* X, const void* H, cons
         }
     }
     if (train_u) {
-        if (!H) LRD_TRY(run_matop(nt(X, in, V, in, Hre, r, T, r, in, dt, false), st));
+        if (!H) {
+            MatOp re = nt(X, in, V, in, Hre, r, T, r, in, dt, false);
+            share_splits(re, region, dt, SPLIT_ACT);
+            LRD_TRY(run_matop(re, st));
+        }
         LRD_TRY(run_matop(wu, st));
     }
     if (train_v) LRD_TRY(run_matop(wv, st));

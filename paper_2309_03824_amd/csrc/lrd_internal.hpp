@@ -56,6 +56,8 @@ hipError_t apply_epilogue(const MatOp& op, hipStream_t st);        // unfused fo
 
 // Workspace floats a MatOp of this shape needs for split-K (0 if it will not be split).
 int choose_splits(int64_t M, int64_t N, int64_t K, bool in_bf16);
+// Split-K count for a product whose result is a narrow bf16 activation (1 = not split).
+int choose_splits_act(int64_t M, int64_t N, int64_t K, bool in_bf16);
 
 // Fused pair  C2[M x N2] = (A[M x K1] . B1[R x K1]^T) . B2[N2 x R]^T : the rank-R intermediate
 // stays on chip; optionally it is also stored (mid_save, [M x R], operand dtype).
@@ -83,7 +85,8 @@ hipError_t column_sums(const void* dY, float* out, int64_t T, int64_t n, bool bf
 // Zero-padding / cropping copy of a row-major matrix (elem_bytes 2 or 4).
 hipError_t copy2d(const void* src, int64_t ld_src, int64_t rows_src, int64_t cols_src, void* dst, int64_t ld_dst,
                   int64_t rows_dst, int64_t cols_dst, int elem_bytes, hipStream_t st);
-hipError_t reduce_partials(const float* partial, float* C, int64_t ldc, int64_t M, int64_t N,
+// C = sum over split-K slices of partial[z][M][N], ascending z; C is fp32 or (c_bf16) bf16.
+hipError_t reduce_partials(const float* partial, void* C, bool c_bf16, int64_t ldc, int64_t M, int64_t N,
                            int splits, hipStream_t st);
 
 }  // namespace lrd

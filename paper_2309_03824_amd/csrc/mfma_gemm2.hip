@@ -482,6 +482,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm2_kernel(Operand A, Operan
     }
 }
 
+// Slices of K a launch really uses (each a whole number of K-steps) and their length.
+inline int effective_splits(const MatOp& op, int* k_per_split)
+{
+    int splits = (op.splits > 1 && op.partial) ? op.splits : 1;
+    int kps = (int)(ceil_div(ceil_div(op.K, splits), BK) * BK);
+    if (k_per_split) *k_per_split = kps;
+    return (int)ceil_div(op.K, kps);
+}
+
 template <int BM, int BN, int WGM, int WGN, int DEPTH, bool A_KM, bool B_KM, class OutT, int G = GATHER_NONE>
 hipError_t launch(const MatOp& op, const Operand& A, const Operand& B, hipStream_t st)
 {
@@ -495,16 +504,16 @@ hipError_t launch(const MatOp& op, const Operand& A, const Operand& B, hipStream
         if (e != hipSuccess) return e;
         lds_allowed = true;
     }
-    int splits = (op.splits > 1 && op.partial) ? op.splits : 1;
-    int kps = (int)(ceil_div(ceil_div(op.K, splits), BK) * BK);
-    splits = (int)ceil_div(op.K, kps);
+    int kps;
+    const int splits = effective_splits(op, &kps);
     float* partial = splits > 1 ? op.partial : nullptr;
+    if (sizeof(OutT) == 4 && !op.out_f32 && !partial) return hipErrorInvalidValue;   // fp32 tiles need the reduce to reach a bf16 C
     dim3 grid((unsigned)ceil_div(op.M, BM), (unsigned)ceil_div(op.N, BN), (unsigned)splits);
     hipLaunchKernelGGL(kern, grid, dim3(NT), lds_bytes, st, A, B, op.cs, (OutT*)op.C, op.ldc, op.bias, partial, (int)op.M,
                        (int)op.N, (int)op.K, kps, op.epilogue, (bf16_t*)op.aux, op.ldaux);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (splits > 1) return reduce_partials(op.partial, (float*)op.C, op.ldc, op.M, op.N, splits, st);
+    if (splits > 1) return reduce_partials(op.partial, op.C, !op.out_f32, op.ldc, op.M, op.N, splits, st);
     return hipSuccess;
 }
 
@@ -514,7 +523,7 @@ inline bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) 
 template <bool A_KM, bool B_KM, class OutT, int G = GATHER_NONE>
 hipError_t by_tile(const MatOp& op, const Operand& A, const Operand& B, hipStream_t st)
 {
-    const int64_t splits = (op.splits > 1 && op.partial) ? op.splits : 1;
+    const int64_t splits = effective_splits(op, nullptr);
     auto wgs = [&](int bm, int bn) { return ceil_div(op.M, bm) * ceil_div(op.N, bn) * splits; };
     if constexpr (sizeof(OutT) == 2 && !A_KM && !B_KM && G == GATHER_NONE) {
         if (op.K >= 1024 && wgs(256, 256) >= 224) return launch<256, 256, 2, 4, 2, false, false, OutT>(op, A, B, st);
@@ -562,7 +571,9 @@ bool mfma_gemm2_supported(const MatOp& op)
         if (op.N % 4 != 0 || op.ldc % 4 != 0 || op.bias) return false;
     } else {
         if (akm) return false;
-        if (op.N % 8 != 0 || op.ldc % 8 != 0 || op.splits > 1) return false;
+        if (op.N % 8 != 0 || op.ldc % 8 != 0) return false;
+        // split-K towards a bf16 result: fp32 partials, rounded once by the reduce; plain products only
+        if (op.splits > 1 && (op.gather != GATHER_NONE || op.bias || op.epilogue != EPI_NONE)) return false;
         if (op.bias && (op.N < 4 || (reinterpret_cast<uintptr_t>(op.bias) & 15u))) return false;
     }
     if (ceil_div(op.N, 64) > 65535) return false;
@@ -591,6 +602,8 @@ hipError_t mfma_gemm2(const MatOp& op, hipStream_t st)
     Operand A{(const bf16_t*)op.A, akm ? op.a_sk : op.a_sm, (int)op.M};
     Operand B{(const bf16_t*)op.B, bkm ? op.b_sk : op.b_sn, (int)op.N};
     if (op.out_f32) return by_tile<true, true, float>(op, A, B, st);
+    if (effective_splits(op, nullptr) > 1)
+        return bkm ? by_tile<false, true, float>(op, A, B, st) : by_tile<false, false, float>(op, A, B, st);
     if (bkm) return by_tile<false, true, bf16_t>(op, A, B, st);
     return by_tile<false, false, bf16_t>(op, A, B, st);
 }
