@@ -25,15 +25,16 @@ int choose_splits(int64_t M, int64_t N, int64_t K, bool in_bf16)
 }
 
 // Products whose result is a [tokens x r] activation (H = X.V^T, dH = dY.U) have few output tiles
-// when r is small and a long K when the wide side of the layer is the reduction.  At T = 8192,
-// r = 192, K = 3072 four slices of 768 (512 workgroups of 128 x 128, two per compute unit) take
-// 22 us plus a 5 us reduce against 38-45 us unsplit; at K = 768 splitting does not pay.
+// when r is small and a long K when the wide side of the layer is the reduction.  While 64 x 64
+// tiles still give every compute unit a workgroup (T = 8192, r = 192: 384 of them) the unsplit
+// kernel is as fast as any split plus its reduce (27.7 us against 25.6-29 us at K = 3072, cold
+// operands), so K is cut only below that, down to slices of 768.
 int choose_splits_act(int64_t M, int64_t N, int64_t K, bool in_bf16)
 {
     if (!in_bf16 || N % 8 != 0) return 1;           // only the aligned MFMA path reduces into bf16
-    const int64_t tiles = ceil_div(M, 128) * ceil_div(N, 128);
-    if (tiles >= 200) return 1;
-    int64_t s = ceil_div(512, tiles);
+    const int64_t t64 = ceil_div(M, 64) * ceil_div(N, 64);
+    if (t64 >= 256) return 1;
+    int64_t s = ceil_div(512, t64);
     const int64_t by_k = K / 768;
     if (s > by_k) s = by_k;
     if (s > 8) s = 8;

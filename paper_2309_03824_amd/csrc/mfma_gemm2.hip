@@ -30,43 +30,78 @@ struct Operand {
     int rows;     // extent along the tile's row index (M for A, N for B)
 };
 
+// Plain (strided) operands are read with buffer loads: the descriptor's base is the tile's first
+// element for this K-step (wave-uniform), each chunk keeps one 32-bit byte offset, and the range
+// check of the descriptor returns zeros for anything past the operand's last element.  A chunk
+// whose row (or column group) does not exist gets an offset no descriptor admits, so static
+// validity costs nothing per step; only the tail of K inside a row needs a mask, and only in the
+// last step (store<true>).
+constexpr uint32_t BUF_FLAGS = 0x00020000u;      // raw buffer, 32-bit data format
+constexpr uint32_t BUF_OOB = 0xFFFFFFF0u;        // >= every num_records used here
+constexpr int64_t BUF_MAX_LD = int64_t(1) << 22; // keeps (256 rows x ld + K) x 2 bytes below BUF_OOB
+
+// Wave-uniform values the compiler cannot always prove uniform; a descriptor built from them stays
+// in scalar registers instead of being looped over per distinct lane value.
+__device__ __forceinline__ uint32_t uni(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ int64_t uni64(int64_t v)
+{
+    uint64_t u = (uint64_t)v;
+    return (int64_t)(((uint64_t)uni((uint32_t)(u >> 32)) << 32) | uni((uint32_t)u));
+}
+__device__ __forceinline__ const char* uni_ptr(const void* p)
+{
+    return reinterpret_cast<const char*>(uni64((int64_t)reinterpret_cast<uintptr_t>(p)));
+}
+
+__device__ __forceinline__ u32x4 buf_load16(const char* base, uint32_t span, uint32_t voff)
+{
+    __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, (int)span, (int)BUF_FLAGS);
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, 0, 0);
+}
+
 // ---- k-contiguous tile: ROWS x BK, chunk c -> row c>>3, k-chunk c&7 ------------------------------
 template <int ROWS, int NT, int DEPTH>
 struct KcTile {
+    static_assert(NT % 8 == 0, "every chunk of a thread has the same k offset");
     static constexpr int CH = (ROWS * 8 + NT - 1) / NT;
     static constexpr bool FULL = (ROWS * 8) % NT == 0;
-    const bf16_t* ptr[CH];
-    bool rowok[CH];
-    int kc8[CH];
+    const char* base;     // first row of the tile, k = 0
+    uint32_t span;        // bytes from base to the end of the tile's last existing row
+    uint32_t voff[CH];
+    int kc8;
     u32x4 st[DEPTH][CH];
 
-    __device__ __forceinline__ void init(const Operand& o, int row0, int tid, const ConvShape&)
+    __device__ __forceinline__ void init(const Operand& o, int row0, int tid, const ConvShape&, int K)
     {
+        base = uni_ptr(o.p + (int64_t)row0 * o.ld);
+        const int rows_here = min(o.rows - row0, ROWS);
+        span = uni((uint32_t)(((int64_t)(rows_here - 1) * o.ld + K) * 2));
+        kc8 = (tid & 7) * 8;
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            int c = tid + i * NT;
-            int row = row0 + (c >> 3);
-            rowok[i] = row < o.rows;
-            kc8[i] = (c & 7) * 8;
-            ptr[i] = o.p + (int64_t)min(row, o.rows - 1) * o.ld;
+            int r = (tid + i * NT) >> 3;
+            voff[i] = r < rows_here ? (uint32_t)((r * o.ld + kc8) * 2) : BUF_OOB;
         }
     }
-    __device__ __forceinline__ void load(int d, int k0, int kend, int tid)
+    __device__ __forceinline__ void load(int d, int k0, int, int tid)
     {
+        const uint32_t kb = uni((uint32_t)k0) * 2u;
+        const char* b = base + kb;
+        const uint32_t left = span - kb;      // k0 < K, so kb < span (a saturating form would leave the scalar unit)
 #pragma unroll
         for (int i = 0; i < CH; ++i)
-            if (FULL || tid + i * NT < ROWS * 8)
-                st[d][i] = *reinterpret_cast<const u32x4*>(ptr[i] + min(k0 + kc8[i], kend - 8));
+            if (FULL || tid + i * NT < ROWS * 8) st[d][i] = buf_load16(b, left, voff[i]);
     }
+    template <bool TAIL>
     __device__ __forceinline__ void store(int d, bf16_t* lds, int k0, int kend, int tid) const
     {
         const u32x4 z = {0u, 0u, 0u, 0u};
+        const bool inside = !TAIL || k0 + kc8 < kend;
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             int c = tid + i * NT;
             if (FULL || c < ROWS * 8)
-                *reinterpret_cast<u32x4*>(lds + (c >> 3) * LDK + (c & 7) * 8) =
-                    (rowok[i] && k0 + kc8[i] < kend) ? st[d][i] : z;
+                *reinterpret_cast<u32x4*>(lds + (c >> 3) * LDK + (c & 7) * 8) = inside ? st[d][i] : z;
         }
     }
 };
@@ -80,31 +115,39 @@ struct KmTile {
     static constexpr int LDM = COLS + 16;                // LDS row length: stride = 8 banks mod 32
     static constexpr int CH = (BK * CPK + NT - 1) / NT;
     static constexpr bool FULL = (BK * CPK) % NT == 0;
-    const bf16_t* ptr[CH];
-    bool colok[CH];
-    int krow[CH];
+    const char* base;     // k = 0, first column of the tile
     int64_t ld;
+    int K, cols_here;     // columns that exist from the tile's first one on
+    uint32_t voff[CH];
+    int krow[CH];
     u32x4 st[DEPTH][CH];
 
-    __device__ __forceinline__ void init(const Operand& o, int col0, int tid, const ConvShape&)
+    __device__ __forceinline__ void init(const Operand& o, int col0, int tid, const ConvShape&, int Kdim)
     {
-        ld = o.ld;
+        ld = uni64(o.ld);
+        K = (int)uni((uint32_t)Kdim);
+        cols_here = (int)uni((uint32_t)(o.rows - col0));
+        base = uni_ptr(o.p + col0);
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             int c = tid + i * NT;
-            int col = col0 + (c % CPK) * 8;
-            colok[i] = col < o.rows;
+            int col = (c % CPK) * 8;
             krow[i] = c / CPK;
-            ptr[i] = o.p + min(col, o.rows - 8);
+            voff[i] = col < cols_here ? (uint32_t)((krow[i] * o.ld + col) * 2) : BUF_OOB;
         }
     }
-    __device__ __forceinline__ void load(int d, int k0, int kend, int tid)
+    __device__ __forceinline__ void load(int d, int k0, int, int tid)
     {
+        // bytes from this step's first k row to the last element of its last existing k row (at most
+        // BK rows) in these columns; rows past K fall outside because ld >= cols_here
+        const int ku = (int)uni((uint32_t)k0);
+        const char* b = base + (int64_t)ku * ld * 2;
+        const uint32_t left = (uint32_t)(min(K - ku, BK) - 1) * ((uint32_t)ld * 2u) + (uint32_t)cols_here * 2u;
 #pragma unroll
         for (int i = 0; i < CH; ++i)
-            if (FULL || tid + i * NT < BK * CPK)
-                st[d][i] = *reinterpret_cast<const u32x4*>(ptr[i] + (int64_t)min(k0 + krow[i], kend - 1) * ld);
+            if (FULL || tid + i * NT < BK * CPK) st[d][i] = buf_load16(b, left, voff[i]);
     }
+    template <bool TAIL>
     __device__ __forceinline__ void store(int d, bf16_t* lds, int k0, int kend, int tid) const
     {
         const u32x4 z = {0u, 0u, 0u, 0u};
@@ -113,7 +156,7 @@ struct KmTile {
             int c = tid + i * NT;
             if (FULL || c < BK * CPK)
                 *reinterpret_cast<u32x4*>(lds + (c / CPK) * LDM + (c % CPK) * 8) =
-                    (colok[i] && k0 + krow[i] < kend) ? st[d][i] : z;
+                    (!TAIL || k0 + krow[i] < kend) ? st[d][i] : z;
         }
     }
 };
@@ -136,7 +179,7 @@ struct ConvRowsTile {
     bool ok[DEPTH][CH];
     u32x4 st[DEPTH][CH];
 
-    __device__ __forceinline__ void init(const Operand& o, int row0, int tid, const ConvShape& shape)
+    __device__ __forceinline__ void init(const Operand& o, int row0, int tid, const ConvShape& shape, int)
     {
         base = o.p;
         cs = shape;
@@ -182,6 +225,7 @@ struct ConvRowsTile {
                 st[d][i] = *reinterpret_cast<const u32x4*>(base + ((int64_t)(img[i] * sh + yy) * sw + xx) * ch + c0);
             }
     }
+    template <bool TAIL>
     __device__ __forceinline__ void store(int d, bf16_t* lds, int, int, int tid) const
     {
         const u32x4 z = {0u, 0u, 0u, 0u};
@@ -209,7 +253,7 @@ struct ConvKmTile {
     bool ok[DEPTH][CH];
     u32x4 st[DEPTH][CH];
 
-    __device__ __forceinline__ void init(const Operand& o, int col0, int tid, const ConvShape& shape)
+    __device__ __forceinline__ void init(const Operand& o, int col0, int tid, const ConvShape& shape, int)
     {
         base = o.p;
         cs = shape;
@@ -255,6 +299,7 @@ struct ConvKmTile {
                 st[d][i] = *reinterpret_cast<const u32x4*>(base + off);
             }
     }
+    template <bool TAIL>
     __device__ __forceinline__ void store(int d, bf16_t* lds, int, int, int tid) const
     {
         const u32x4 z = {0u, 0u, 0u, 0u};
@@ -339,7 +384,7 @@ constexpr int gemm2_lds_bytes()
 }
 
 template <int BM, int BN, int WGM, int WGN, int DEPTH, bool A_KM, bool B_KM, class OutT, int G>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm2_kernel(Operand A, Operand B, ConvShape cs, OutT* __restrict__ C, int64_t ldc,
+__global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm2_kernel(Operand A, Operand B, ConvShape cs, OutT* __restrict__ C, int64_t ldc,
                                                                const float* __restrict__ bias, float* __restrict__ partial,
                                                                int M, int N, int K, int k_per_split, int epilogue,
                                                                bf16_t* __restrict__ aux, int64_t ldaux)
@@ -368,21 +413,53 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm2_kernel(Operand A, Operan
 
     typename TileSel<BM, NT, DEPTH, A_KM, G, true>::type ta;
     typename TileSel<BN, NT, DEPTH, B_KM, G, false>::type tb;
-    ta.init(A, m0, tid, cs);
-    tb.init(B, n0, tid, cs);
+    ta.init(A, m0, tid, cs, K);
+    tb.init(B, n0, tid, cs, K);
 
+    int kt0 = 0;
+    if (nk >= 2 * DEPTH) {
+        // Long reductions.  Prologue and steady state are straight-line code: the loads of DEPTH steps
+        // are issued unconditionally and stay in flight from one iteration to the next (a branch in
+        // here makes the compiler wait for every outstanding load at the top of each step).
 #pragma unroll
-    for (int d = 0; d < DEPTH; ++d)
-        if (d < nk) {
+        for (int d = 0; d < DEPTH; ++d) {
             ta.load(d, kbeg + d * BK, kend, tid);
             tb.load(d, kbeg + d * BK, kend, tid);
         }
-    if (nk > 0) {
-        ta.store(0, lds, kbeg, kend, tid);
-        tb.store(0, lds + A_ELEMS, kbeg, kend, tid);
+        ta.template store<false>(0, lds, kbeg, kend, tid);
+        tb.template store<false>(0, lds + A_ELEMS, kbeg, kend, tid);
+        __syncthreads();
+        // Each step issues the loads of step +DEPTH, multiplies, and hands step +1 to LDS.
+        for (; kt0 + 2 * DEPTH <= nk; kt0 += DEPTH) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                const int kt = kt0 + d;
+                bf16_t* cur = lds + (kt & 1) * STAGE;
+                bf16_t* nxt = lds + ((kt + 1) & 1) * STAGE;
+                ta.load(d, kbeg + (kt + DEPTH) * BK, kend, tid);
+                tb.load(d, kbeg + (kt + DEPTH) * BK, kend, tid);
+                __builtin_amdgcn_sched_barrier(0);   // keep the loads first: the scheduler otherwise sinks them below the MFMAs
+                mma_step<TM, TN, A_KM, B_KM, BM + 16, BN + 16>(acc, cur, wm * WTM, cur + A_ELEMS, wn * WTN, lane);
+                ta.template store<false>((d + 1) % DEPTH, nxt, kbeg + (kt + 1) * BK, kend, tid);
+                tb.template store<false>((d + 1) % DEPTH, nxt + A_ELEMS, kbeg + (kt + 1) * BK, kend, tid);
+                __syncthreads();
+            }
+        }
+    } else {
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d)
+            if (d < nk) {
+                ta.load(d, kbeg + d * BK, kend, tid);
+                tb.load(d, kbeg + d * BK, kend, tid);
+            }
+        if (nk > 0) {
+            ta.template store<true>(0, lds, kbeg, kend, tid);
+            tb.template store<true>(0, lds + A_ELEMS, kbeg, kend, tid);
+        }
+        __syncthreads();
     }
-    __syncthreads();
-    for (int kt0 = 0; kt0 < nk; kt0 += DEPTH) {
+    // Drain: the last (up to 2 * DEPTH - 1) steps, which stop loading and then stop storing.
+    for (; kt0 < nk; kt0 += DEPTH) {
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
             const int kt = kt0 + d;
@@ -395,8 +472,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm2_kernel(Operand A, Operan
                 }
                 mma_step<TM, TN, A_KM, B_KM, BM + 16, BN + 16>(acc, cur, wm * WTM, cur + A_ELEMS, wn * WTN, lane);
                 if (kt + 1 < nk) {
-                    ta.store((d + 1) % DEPTH, nxt, kbeg + (kt + 1) * BK, kend, tid);
-                    tb.store((d + 1) % DEPTH, nxt + A_ELEMS, kbeg + (kt + 1) * BK, kend, tid);
+                    ta.template store<true>((d + 1) % DEPTH, nxt, kbeg + (kt + 1) * BK, kend, tid);
+                    tb.template store<true>((d + 1) % DEPTH, nxt + A_ELEMS, kbeg + (kt + 1) * BK, kend, tid);
                 }
                 __syncthreads();
             }
@@ -577,6 +654,7 @@ bool mfma_gemm2_supported(const MatOp& op)
         if (op.bias && (op.N < 4 || (reinterpret_cast<uintptr_t>(op.bias) & 15u))) return false;
     }
     if (ceil_div(op.N, 64) > 65535) return false;
+    if (op.gather == GATHER_NONE && ((akm ? op.a_sk : op.a_sm) > BUF_MAX_LD || (bkm ? op.b_sk : op.b_sn) > BUF_MAX_LD)) return false;
     if (op.epilogue != EPI_NONE && (op.out_f32 || !op.aux || !al16(op.aux) || op.ldaux % 8 != 0)) return false;
     return true;
 }
