@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the reported kernel from rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000
 # (profiles/gemm2_ffn_stack_hbm_traffic.md).  Set to None whenever that kernel or its tiling changes.
-GEMM2_64_FWD_DOWN_TRAFFIC_BYTES = 40.6e6
+GEMM2_FWD_UP_TRAFFIC_BYTES = 66.5e6
 
 
 def layer_flops(T, n_in, n_out, r, mask, want_dx=True):
@@ -82,10 +82,10 @@ class Stack:
         self.probe = None     # optional (start_event, end_event) list filled around one call class
 
     def _probe(self):
-        """Arms the library's one-shot event probe for the next H = X.V^T product kernel."""
+        """Arms the library's one-shot event probe for the next Y = H.U^T product kernel."""
         if self.probe is not None:
             pair = (self.lrd.HipEvent(), self.lrd.HipEvent())
-            self.lrd.profile_next(self.lrd.ROLE_FWD_DOWN, *pair)
+            self.lrd.profile_next(self.lrd.ROLE_FWD_UP, *pair)
             self.probe.append(pair)
 
     def forward(self):
@@ -387,16 +387,18 @@ def main():
     flops = (flops_even * n_even + flops_odd * (args.steps - n_even)) / args.steps
     tflops = flops / (ms * 1e-3) / 1e12
 
-    # Dominant kernel by total time (see profiles/): the 64x64-tile bf16 MFMA product kernel in its
-    # forward role H = X.V^T (one launch per lrd_linear_fwd call, two shapes: in = 768 and in = 3072).
+    # Dominant kernel by total time (see profiles/): the eight-wave 128x128-tile bf16 MFMA product kernel
+    # in its forward role Y = H.U^T (one launch per lrd_linear_fwd call, two shapes: out = 3072 with the
+    # GELU epilogue, which writes the pre-activation and the activation, and out = 768 without).
     # It is bracketed by HIP events inside the timed region through lrd_profile_next.
-    # Algorithmic bytes per launch: X read once, V read once, H written once (bf16).
+    # Algorithmic bytes per launch: H and U read once, Y (and the activation) written once, all bf16.
     k_us = sum(s.elapsed_us(e) for s, e in probe) / len(probe)
-    k_bytes = sum(2 * (T_TOKENS * n_in + rank * n_in + T_TOKENS * rank) for n_in in (D_MODEL, D_FF)) / 2
+    k_bytes = (2 * (T_TOKENS * rank + D_FF * rank + 2 * T_TOKENS * D_FF) +
+               2 * (T_TOKENS * rank + D_MODEL * rank + T_TOKENS * D_MODEL)) / 2
     achieved = k_bytes / (k_us * 1e-6) / 1e9
     roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved / HBM_PEAK_GBS,
-                    traffic=GEMM2_64_FWD_DOWN_TRAFFIC_BYTES,
-                    kernel="gemm2_kernel<64,64,2,2,2,false,false,bf16> as H = X.V^T (lrd_linear_fwd)",
+                    traffic=GEMM2_FWD_UP_TRAFFIC_BYTES,
+                    kernel="gemm2_kernel<128,128,2,4,2,false,false,bf16> as Y = H.U^T (lrd_linear_fwd / lrd_linear_fwd_act)",
                     avg_us=k_us, launches=len(probe), bytes_per_launch=k_bytes)
 
     out = dict(metric="decomposed-layer fwd+bwd throughput (12-block encoder FFN stack)", value=tflops,
