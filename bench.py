@@ -276,6 +276,88 @@ def rank_sweep(args, torch, lrd):
                           points=points)))
 
 
+def layer_tables(args, torch, lrd):
+    """Configs 4 and 5, layer by layer: the four ResNet-style 3x3 stages (N = 128, Tucker ranks C/2 and
+    the raw ranks next to them, core frozen / 1x1s frozen / nothing frozen, beside the dense conv) and
+    the transformer projections 1024->1024, 1024->4096, 4096->1024 (8192 tokens, r = 256).
+    Timing only (parity of these shapes is covered by the tests); prints one JSON line."""
+    bf = torch.bfloat16
+    gen = torch.Generator(device="cuda").manual_seed(230903824 + 4)
+
+    def rnd(*shape, scale=1.0):
+        return (torch.randn(*shape, device="cuda", generator=gen) * scale).to(bf)
+
+    def timeit(fn, iters=10):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        for _ in range(iters):
+            fn()
+        e.record()
+        torch.cuda.synchronize()
+        return s.elapsed_time(e) * 1e3 / iters
+
+    def empty(*shape, dt=bf):
+        return torch.empty(*shape, dtype=dt, device="cuda")
+
+    conv = []
+    N, k = 128, 3
+    for C, hw in ((64, 56), (128, 28), (256, 14), (512, 7)):
+        X, dY = rnd(N, hw, hw, C), rnd(N, hw, hw, C)
+        Y, dX = empty(N, hw, hw, C), empty(N, hw, hw, C)
+        P = N * hw * hw
+        stage = dict(C=C, hw=hw, pixels=P, ranks=[])
+        for r in (C // 2 - 1, C // 2, C // 2 + 1):
+            g = lrd.conv_geom(N, hw, hw, C, C, r, r, k, 1, 1)
+            P1, G, P2 = rnd(r, C, scale=C ** -0.5), rnd(r, k, k, r, scale=(k * k * r) ** -0.5), rnd(C, r, scale=r ** -0.5)
+            A, B = empty(N, hw, hw, r), empty(N, hw, hw, r)
+            dP1, dG, dP2 = empty(r, C, dt=torch.float32), empty(r, k, k, r, dt=torch.float32), empty(C, r, dt=torch.float32)
+            ws = torch.empty(lrd.tucker_conv_workspace_bytes(g, lrd.BF16, 0) + 256, dtype=torch.uint8, device="cuda")
+            fwd = timeit(lambda: lrd.tucker_conv_fwd(X, P1, G, P2, Y, A, B, g, ws))
+            row = dict(r=r, fwd_us=fwd)
+            for name, mask in (("core", 0b010), ("1x1", 0b101), ("none", 0)):
+                row[f"bwd_us_frozen_{name}"] = timeit(
+                    lambda: lrd.tucker_conv_bwd(dY, X, A, B, P1, G, P2, dX, dP1, dG, dP2, mask, g, ws))
+            f_fwd = 2.0 * P * (C * r + k * k * r * r + r * C)
+            f_bwd_core = 2.0 * f_fwd - 2.0 * P * k * k * r * r
+            row["tflops_fwd_bwd_core_frozen"] = (f_fwd + f_bwd_core) / ((fwd + row["bwd_us_frozen_core"]) * 1e-6) / 1e12
+            # algorithmic bytes, core frozen: X, Y, dY, dX once each; A, B written and read back; factors; fp32 1x1 gradients
+            byts = 2.0 * (4 * P * C + 4 * P * r) + 2.0 * (2 * C * r + k * k * r * r) + 4.0 * 2 * C * r
+            row["hbm_frac_fwd_bwd_core_frozen"] = byts / ((fwd + row["bwd_us_frozen_core"]) * 1e-6) / 1e9 / HBM_PEAK_GBS
+            stage["ranks"].append(row)
+        g = lrd.conv_geom(N, hw, hw, C, C, C // 2, C // 2, k, 1, 1)
+        W, dW = rnd(C, k, k, C, scale=(k * k * C) ** -0.5), empty(C, k, k, C, dt=torch.float32)
+        wsd = torch.empty(lrd.dense_conv_workspace_bytes(g, lrd.BF16) + 256, dtype=torch.uint8, device="cuda")
+        stage["dense_fwd_us"] = timeit(lambda: lrd.dense_conv_fwd(X, W, Y, g, wsd), 5)
+        stage["dense_bwd_us"] = timeit(lambda: lrd.dense_conv_bwd(dY, X, W, dX, dW, g, wsd), 5)
+        stage["dense_tflops"] = 6.0 * P * k * k * C * C / ((stage["dense_fwd_us"] + stage["dense_bwd_us"]) * 1e-6) / 1e12
+        conv.append(stage)
+
+    lin = []
+    T, r = 8192, 256
+    for n_in, n_out in ((1024, 1024), (1024, 4096), (4096, 1024)):
+        X, dY = rnd(T, n_in), rnd(T, n_out)
+        V, U = rnd(r, n_in, scale=n_in ** -0.5), rnd(n_out, r, scale=r ** -0.5)
+        Y, H, dX = empty(T, n_out), empty(T, r), empty(T, n_in)
+        dV, dU = empty(r, n_in, dt=torch.float32), empty(n_out, r, dt=torch.float32)
+        ws = torch.empty(lrd.linear_workspace_bytes(T, n_in, n_out, r, lrd.BF16, 0) + 256, dtype=torch.uint8, device="cuda")
+        fwd = timeit(lambda: lrd.linear_fwd(X, V, U, None, Y, H, ws), 20)
+        row = {"in": n_in, "out": n_out, "r": r, "fwd_us": fwd}
+        for name, mask in (("V", 1), ("U", 2), ("none", 0)):
+            row[f"bwd_us_frozen_{name}"] = timeit(lambda: lrd.linear_bwd(dY, X, H, V, U, dX, dV, dU, None, mask, ws), 20)
+        f_v = 2.0 * T * r * (n_in + n_out) * 2 + 2.0 * T * r * n_out
+        row["tflops_fwd_bwd_V_frozen"] = f_v / ((fwd + row["bwd_us_frozen_V"]) * 1e-6) / 1e12
+        W, dW = rnd(n_out, n_in, scale=n_in ** -0.5), empty(n_out, n_in, dt=torch.float32)
+        wsd = torch.empty(lrd.dense_linear_workspace_bytes(T, n_in, n_out, lrd.BF16) + 256, dtype=torch.uint8, device="cuda")
+        row["dense_fwd_us"] = timeit(lambda: lrd.dense_linear_fwd(X, W, None, Y, wsd), 10)
+        row["dense_bwd_us"] = timeit(lambda: lrd.dense_linear_bwd(dY, X, W, dX, dW, wsd), 10)
+        lin.append(row)
+    print(json.dumps(dict(metric="layer tables: config 4 (Tucker 3x3 stages, N = 128) and config 5 (projections, 8192 tokens, r = 256), "
+                                 "bf16, microseconds per call", conv_stages=conv, projections=lin)))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -285,6 +367,8 @@ def main():
     ap.add_argument("--no-comparators", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
     ap.add_argument("--rank-sweep", action="store_true", help="run the rank sweep (config 3) instead of the FFN stack")
+    ap.add_argument("--layer-tables", action="store_true",
+                    help="time the Tucker conv stages (config 4) and the transformer projections (config 5) instead")
     ap.add_argument("--sweep-step", type=int, default=16)
     ap.add_argument("--sweep-iters", type=int, default=5)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -308,6 +392,9 @@ def main():
 
     if args.rank_sweep:
         rank_sweep(args, torch, lrd)
+        return
+    if args.layer_tables:
+        layer_tables(args, torch, lrd)
         return
 
     if args.calibrate_copy:

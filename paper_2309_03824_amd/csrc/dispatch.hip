@@ -20,7 +20,7 @@ int choose_splits(int64_t M, int64_t N, int64_t K, bool in_bf16)
     int64_t s = t128 >= 24 ? ceil_div(480, t128) : ceil_div(432, t64);
     const int64_t by_k = K / 256;          // keep at least 256 reduction steps per slice
     if (s > by_k) s = by_k;
-    if (s > 64) s = 64;
+    if (s > 512) s = 512;
     return s < 2 ? 1 : (int)s;
 }
 

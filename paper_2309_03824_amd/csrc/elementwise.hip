@@ -114,6 +114,31 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
     }
 }
 
+// The same sum for small fp32 results cut into many slices (weight gradients of narrow layers, whose
+// reduction runs over all pixels): one thread per output would leave most of the chip idle and walk
+// the slices one after the other, so 16 threads share a group of 4 outputs, thread l adds slices
+// l, l + 16, ... in ascending order and the 16 sums are combined in ascending l.  Still a fixed order.
+__global__ __launch_bounds__(256) void reduce_partials_wide_kernel(const float* __restrict__ partial, float* __restrict__ C,
+                                                                   int64_t ldc, int64_t M, int64_t N, int splits)
+{
+    __shared__ f32x4 part[16][17];
+    const int64_t total = M * N, groups = total / 4;
+    const int gl = threadIdx.x & 15, l = threadIdx.x >> 4;
+    const int64_t g = (int64_t)blockIdx.x * 16 + gl;
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    if (g < groups)
+        for (int z = l; z < splits; z += 16) s += *reinterpret_cast<const f32x4*>(partial + (int64_t)z * total + g * 4);
+    part[l][gl] = s;
+    __syncthreads();
+    if (l == 0 && g < groups) {
+        f32x4 t = part[0][gl];
+#pragma unroll
+        for (int q = 1; q < 16; ++q) t += part[q][gl];
+        const int64_t i = g * 4;
+        *reinterpret_cast<f32x4*>(C + (i / N) * ldc + (i % N)) = t;
+    }
+}
+
 // dst[i][j] (rows_d x cols_d, leading dimension ldd) = src[i][j] where it exists (i < rows_s, j < cols_s), else 0.
 template <class T>
 __global__ __launch_bounds__(256) void copy2d_kernel(const T* __restrict__ src, int64_t lds_, int64_t rows_s, int64_t cols_s,
@@ -191,7 +216,10 @@ hipError_t reduce_partials(const float* partial, void* C, bool c_bf16, int64_t l
             hipLaunchKernelGGL((reduce_partials_kernel<1, bf16_t>), dim3(blocks_for(M * N)), dim3(256), 0, st, partial,
                                (bf16_t*)C, ldc, M, N, splits);
     } else {
-        if (al && N % 4 == 0 && ldc % 4 == 0)
+        if (al && N % 4 == 0 && ldc % 4 == 0 && splits >= 16 && M * N / 4 < 256 * 256)
+            hipLaunchKernelGGL(reduce_partials_wide_kernel, dim3((unsigned)ceil_div(M * N / 4, 16)), dim3(256), 0, st, partial,
+                               (float*)C, ldc, M, N, splits);
+        else if (al && N % 4 == 0 && ldc % 4 == 0)
             hipLaunchKernelGGL((reduce_partials_kernel<4, float>), dim3(blocks_for(M * N / 4)), dim3(256), 0, st, partial,
                                (float*)C, ldc, M, N, splits);
         else
