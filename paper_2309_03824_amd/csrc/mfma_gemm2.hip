@@ -71,7 +71,7 @@ struct KcTile {
     int kc8;
     u32x4 st[DEPTH][CH];
 
-    __device__ __forceinline__ void init(const Operand& o, int row0, int tid, const ConvShape&, int K)
+    __device__ __forceinline__ void init(const Operand& o, int row0, int tid, const ConvShape&, int K, int)
     {
         base = uni_ptr(o.p + (int64_t)row0 * o.ld);
         const int rows_here = min(o.rows - row0, ROWS);
@@ -122,7 +122,7 @@ struct KmTile {
     int krow[CH];
     u32x4 st[DEPTH][CH];
 
-    __device__ __forceinline__ void init(const Operand& o, int col0, int tid, const ConvShape&, int Kdim)
+    __device__ __forceinline__ void init(const Operand& o, int col0, int tid, const ConvShape&, int Kdim, int)
     {
         ld = uni64(o.ld);
         K = (int)uni((uint32_t)Kdim);
@@ -162,27 +162,43 @@ struct KmTile {
 };
 
 // ---- implicit-GEMM operands of a k x k convolution on NHWC data ---------------------------------
-// Same LDS layouts and the same clamp-the-address / zero-at-store rule as the plain tiles; only
-// the address of a 16-byte chunk comes from the tap geometry.  Channel counts are multiples of 8
-// on this path, so a chunk never straddles two taps.
+// Same LDS layouts as the plain tiles; the address of a 16-byte chunk comes from the tap geometry,
+// out-of-image taps and tails are clamped to a legal address and zeroed when the chunk is written
+// to LDS.  Channel counts are multiples of 8 on this path, so a chunk never straddles two taps.
+// K-steps are loaded strictly in order (k0 = kbeg, kbeg + BK, ...), so the decomposition of k into
+// (tap, channel) or (image, y, x) is kept as state and advanced by BK after every load: the only
+// integer divisions are in init().
+
+// floor(t / d) for 0 <= t * d < 65536 by multiplication (d < 32 and t <= d * d + 8 here).
+__device__ __forceinline__ int small_div(int t, int magic) { return (t * magic) >> 16; }
 
 // A operand, k-contiguous.  FWD:   row = output pixel, k = (u, v, i), reads X[n, y*s+u-p, x*s+v-p, i].
 //                           DGRAD: row = input pixel,  k = (u, v, o), reads dY[n, (a+p-u)/s, (b+p-v)/s, o].
 template <int ROWS, int NT, int DEPTH, bool DGRAD>
 struct ConvRowsTile {
+    static_assert(NT % 8 == 0, "every chunk of a thread has the same k offset");
     static constexpr int CH = (ROWS * 8 + NT - 1) / NT;
     static constexpr bool FULL = (ROWS * 8) % NT == 0;
     const bf16_t* base;
     ConvShape cs;
-    int img[CH], py[CH], px[CH], kc8[CH];
+    int img[CH], py[CH], px[CH];
     bool rowok[CH];
+    int kc8, tap, c0;         // this thread's k of the next load, as (tap, channel); same for all its chunks
+    int ch, q_tap, r_ch, magic;
     bool ok[DEPTH][CH];
     u32x4 st[DEPTH][CH];
 
-    __device__ __forceinline__ void init(const Operand& o, int row0, int tid, const ConvShape& shape, int)
+    __device__ __forceinline__ void init(const Operand& o, int row0, int tid, const ConvShape& shape, int, int kbeg)
     {
         base = o.p;
         cs = shape;
+        ch = DGRAD ? cs.O : cs.I;            // channels of the tensor being gathered
+        q_tap = BK / ch;
+        r_ch = BK - q_tap * ch;
+        magic = (65536 + cs.k - 1) / cs.k;
+        kc8 = (tid & 7) * 8;
+        tap = (kbeg + kc8) / ch;
+        c0 = (kbeg + kc8) - tap * ch;
         const int gw = DGRAD ? cs.W : cs.Wo, gh = DGRAD ? cs.H : cs.Ho;
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
@@ -190,7 +206,6 @@ struct ConvRowsTile {
             int row = row0 + (c >> 3);
             rowok[i] = row < o.rows;
             row = min(row, o.rows - 1);
-            kc8[i] = (c & 7) * 8;
             px[i] = row % gw;
             int q = row / gw;
             py[i] = q % gh;
@@ -199,31 +214,41 @@ struct ConvRowsTile {
     }
     __device__ __forceinline__ void load(int d, int k0, int kend, int tid)
     {
-        const int ch = DGRAD ? cs.O : cs.I;            // channels of the tensor being gathered
         const int sh = DGRAD ? cs.Ho : cs.H, sw = DGRAD ? cs.Wo : cs.W;
+        const int u = small_div(tap, magic), v = tap - u * cs.k;
+        const bool kin = k0 + kc8 < kend;
 #pragma unroll
         for (int i = 0; i < CH; ++i)
             if (FULL || tid + i * NT < ROWS * 8) {
-                int k = min(k0 + kc8[i], kend - 8);
-                int tap = k / ch, c0 = k - tap * ch;
-                int u = tap / cs.k, v = tap - u * cs.k;
                 int yy, xx;
                 bool inside;
                 if (DGRAD) {
                     int ys = py[i] + cs.pad - u, xs = px[i] + cs.pad - v;
-                    yy = ys / cs.stride;
-                    xx = xs / cs.stride;
-                    inside = ys >= 0 && xs >= 0 && yy * cs.stride == ys && xx * cs.stride == xs && yy < sh && xx < sw;
+                    if (cs.stride == 1) {
+                        yy = ys;
+                        xx = xs;
+                        inside = ys >= 0 && xs >= 0 && yy < sh && xx < sw;
+                    } else {
+                        yy = ys / cs.stride;
+                        xx = xs / cs.stride;
+                        inside = ys >= 0 && xs >= 0 && yy * cs.stride == ys && xx * cs.stride == xs && yy < sh && xx < sw;
+                    }
                 } else {
                     yy = py[i] * cs.stride + u - cs.pad;
                     xx = px[i] * cs.stride + v - cs.pad;
                     inside = yy >= 0 && xx >= 0 && yy < sh && xx < sw;
                 }
-                ok[d][i] = inside && rowok[i] && k0 + kc8[i] < kend;
-                yy = min(max(yy, 0), sh - 1);
+                ok[d][i] = inside && rowok[i] && kin;
+                yy = min(max(yy, 0), sh - 1);          // also covers taps past the last one (tail of K)
                 xx = min(max(xx, 0), sw - 1);
                 st[d][i] = *reinterpret_cast<const u32x4*>(base + ((int64_t)(img[i] * sh + yy) * sw + xx) * ch + c0);
             }
+        c0 += r_ch;
+        tap += q_tap;
+        if (c0 >= ch) {
+            c0 -= ch;
+            ++tap;
+        }
     }
     template <bool TAIL>
     __device__ __forceinline__ void store(int d, bf16_t* lds, int, int, int tid) const
@@ -248,55 +273,86 @@ struct ConvKmTile {
     static constexpr bool FULL = (BK * CPK) % NT == 0;
     const bf16_t* base;
     ConvShape cs;
-    int krow[CH], c0[CH], tu[CH], tv[CH];
+    int c0[CH], tu[CH], tv[CH];
     bool colok[CH];
+    // k of the next load, per chunk.  DGRAD: (tap, o) in s1, s0.  WGRAD: output pixel as (n, y, x) in s2, s1, s0.
+    int s0[CH], s1[CH], s2[CH], kk[CH];
+    int d0, d1, d2;           // BK in the same mixed radix
     bool ok[DEPTH][CH];
     u32x4 st[DEPTH][CH];
 
-    __device__ __forceinline__ void init(const Operand& o, int col0, int tid, const ConvShape& shape, int)
+    __device__ __forceinline__ void init(const Operand& o, int col0, int tid, const ConvShape& shape, int, int kbeg)
     {
         base = o.p;
         cs = shape;
+        if (WGRAD) {
+            d2 = BK / (cs.Ho * cs.Wo);
+            int rem = BK - d2 * cs.Ho * cs.Wo;
+            d1 = rem / cs.Wo;
+            d0 = rem - d1 * cs.Wo;
+        } else {
+            d2 = 0;
+            d1 = BK / cs.O;
+            d0 = BK - d1 * cs.O;
+        }
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             int c = tid + i * NT;
             int col = col0 + (c % CPK) * 8;
             colok[i] = col < o.rows;
             col = min(col, o.rows - 8);
-            krow[i] = c / CPK;
+            const int k = kbeg + c / CPK;
+            kk[i] = k;
             if (WGRAD) {
                 int tap = col / cs.I;
                 c0[i] = col - tap * cs.I;
                 tu[i] = tap / cs.k;
                 tv[i] = tap - tu[i] * cs.k;
+                s0[i] = k % cs.Wo;
+                int q = k / cs.Wo;
+                s1[i] = q % cs.Ho;
+                s2[i] = q / cs.Ho;
             } else {
                 c0[i] = col;
                 tu[i] = tv[i] = 0;
+                s1[i] = k / cs.O;
+                s0[i] = k - s1[i] * cs.O;
+                s2[i] = 0;
             }
         }
     }
-    __device__ __forceinline__ void load(int d, int k0, int kend, int tid)
+    __device__ __forceinline__ void load(int d, int, int kend, int tid)
     {
 #pragma unroll
         for (int i = 0; i < CH; ++i)
             if (FULL || tid + i * NT < BK * CPK) {
-                int k = min(k0 + krow[i], kend - 1);
+                const bool kin = kk[i] < kend;
                 bool inside = true;
                 int64_t off;
                 if (WGRAD) {
-                    int x = k % cs.Wo, q = k / cs.Wo;
-                    int y = q % cs.Ho, n = q / cs.Ho;
-                    int yy = y * cs.stride + tu[i] - cs.pad, xx = x * cs.stride + tv[i] - cs.pad;
+                    int yy = s1[i] * cs.stride + tu[i] - cs.pad, xx = s0[i] * cs.stride + tv[i] - cs.pad;
                     inside = yy >= 0 && xx >= 0 && yy < cs.H && xx < cs.W;
                     yy = min(max(yy, 0), cs.H - 1);
                     xx = min(max(xx, 0), cs.W - 1);
+                    int n = min(s2[i], cs.N - 1);           // pixels past the last one (tail of K) stay in the tensor
                     off = ((int64_t)(n * cs.H + yy) * cs.W + xx) * cs.I + c0[i];
                 } else {
-                    int tap = k / cs.O, o = k - tap * cs.O;
-                    off = ((int64_t)o * cs.k * cs.k + tap) * cs.I + c0[i];
+                    int tap = min(s1[i], cs.k * cs.k - 1);  // likewise for taps past the last one
+                    off = ((int64_t)s0[i] * cs.k * cs.k + tap) * cs.I + c0[i];
                 }
-                ok[d][i] = inside && colok[i] && k0 + krow[i] < kend;
+                ok[d][i] = inside && colok[i] && kin;
                 st[d][i] = *reinterpret_cast<const u32x4*>(base + off);
+                // advance this chunk's k by BK
+                kk[i] += BK;
+                s0[i] += d0;
+                s1[i] += d1;
+                if (WGRAD) {
+                    if (s0[i] >= cs.Wo) { s0[i] -= cs.Wo; ++s1[i]; }
+                    s2[i] += d2;
+                    if (s1[i] >= cs.Ho) { s1[i] -= cs.Ho; ++s2[i]; }
+                } else {
+                    if (s0[i] >= cs.O) { s0[i] -= cs.O; ++s1[i]; }
+                }
             }
     }
     template <bool TAIL>
@@ -483,8 +539,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm2_kernel(Operand A, Ope
 
     typename TileSel<BM, NT, DEPTH, A_KM, G, true>::type ta;
     typename TileSel<BN, NT, DEPTH, B_KM, G, false>::type tb;
-    ta.init(A, m0, tid, cs, K);
-    tb.init(B, n0, tid, cs, K);
+    ta.init(A, m0, tid, cs, K, kbeg);
+    tb.init(B, n0, tid, cs, K, kbeg);
 
     int kt0 = 0;
     if (nk >= 2 * DEPTH) {
@@ -651,7 +707,7 @@ bool mfma_gemm2_supported(const MatOp& op)
         if (!bkm && op.b_sn % 8 != 0) return false;
     } else {
         // implicit-GEMM convolution: channel counts must keep every 16-byte chunk inside one tap
-        if (op.cs.I % 8 != 0 || op.cs.O % 8 != 0 || op.cs.k < 1 || op.cs.stride < 1) return false;
+        if (op.cs.I % 8 != 0 || op.cs.O % 8 != 0 || op.cs.k < 1 || op.cs.k > 31 || op.cs.stride < 1) return false;
         if ((int64_t)op.cs.N * op.cs.H * op.cs.W * op.cs.I >= (int64_t(1) << 31)) return false;
         if ((int64_t)op.cs.N * op.cs.Ho * op.cs.Wo * op.cs.O >= (int64_t(1) << 31)) return false;
         if (op.gather == GATHER_CONV_FWD) {
