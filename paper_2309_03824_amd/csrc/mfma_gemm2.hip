@@ -677,7 +677,7 @@ hipError_t by_tile(const MatOp& op, const Operand& A, const Operand& B, hipStrea
     if constexpr (sizeof(OutT) == 2 && !A_KM && !B_KM && G == GATHER_NONE) {
         if (op.K >= 1024 && wgs(256, 256) >= 224) return launch<256, 256, 2, 4, 2, false, false, OutT>(op, A, B, st);
     }
-    if (wgs(128, 128) >= 200 || (op.M > 64 && op.N > 64 && wgs(64, 64) > 2048)) {
+    if (op.M > 64 && op.N > 64 && (wgs(128, 128) >= 200 || wgs(64, 64) > 2048)) {
         // Short reductions with bf16 results (K = rank: second product of a forward pair or of a data
         // gradient) are dominated by the epilogue; eight waves per tile overlap it better than four
         // (31.8 against 36.0 us at 8192 x 3072 x 192 with the GELU epilogue).
