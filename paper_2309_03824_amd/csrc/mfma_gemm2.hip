@@ -677,6 +677,11 @@ hipError_t by_tile(const MatOp& op, const Operand& A, const Operand& B, hipStrea
     if constexpr (sizeof(OutT) == 2 && !A_KM && !B_KM && G == GATHER_NONE) {
         if (op.K >= 1024 && wgs(256, 256) >= 224) return launch<256, 256, 2, 4, 2, false, false, OutT>(op, A, B, st);
     }
+    // Results at most 32 columns wide (1x1 and core convolutions at Tucker ranks <= 32): a 128 x 32 tile
+    // does a quarter of the MFMA and LDS work of a 128 x 128 one (15 against 23 us at 401408 x 32 x 64).
+    if constexpr (sizeof(OutT) == 2 && !A_KM && G != GATHER_CONV_WGRAD) {
+        if (op.N <= 32 && wgs(128, 32) >= 256) return launch<128, 32, 4, 1, 2, false, B_KM, OutT, G>(op, A, B, st);
+    }
     if (op.M > 64 && op.N > 64 && (wgs(128, 128) >= 200 || wgs(64, 64) > 2048)) {
         // Short reductions with bf16 results (K = rank: second product of a forward pair or of a data
         // gradient) are dominated by the epilogue; eight waves per tile overlap it better than four
