@@ -116,24 +116,27 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
 
 // The same sum for small fp32 results cut into many slices (weight gradients of narrow layers, whose
 // reduction runs over all pixels): one thread per output would leave most of the chip idle and walk
-// the slices one after the other, so 16 threads share a group of 4 outputs, thread l adds slices
-// l, l + 16, ... in ascending order and the 16 sums are combined in ascending l.  Still a fixed order.
+// the slices one after the other, so LANES threads share a group of 4 outputs, thread l adds slices
+// l, l + LANES, ... in ascending order and the LANES sums are combined in ascending l.  Still a
+// fixed order.
+template <int LANES>
 __global__ __launch_bounds__(256) void reduce_partials_wide_kernel(const float* __restrict__ partial, float* __restrict__ C,
                                                                    int64_t ldc, int64_t M, int64_t N, int splits)
 {
-    __shared__ f32x4 part[16][17];
+    constexpr int GROUPS = 256 / LANES;       // groups of 4 outputs per block
+    __shared__ f32x4 part[LANES][GROUPS + 1];
     const int64_t total = M * N, groups = total / 4;
-    const int gl = threadIdx.x & 15, l = threadIdx.x >> 4;
-    const int64_t g = (int64_t)blockIdx.x * 16 + gl;
+    const int gl = threadIdx.x % GROUPS, l = threadIdx.x / GROUPS;
+    const int64_t g = (int64_t)blockIdx.x * GROUPS + gl;
     f32x4 s = {0.f, 0.f, 0.f, 0.f};
     if (g < groups)
-        for (int z = l; z < splits; z += 16) s += *reinterpret_cast<const f32x4*>(partial + (int64_t)z * total + g * 4);
+        for (int z = l; z < splits; z += LANES) s += *reinterpret_cast<const f32x4*>(partial + (int64_t)z * total + g * 4);
     part[l][gl] = s;
     __syncthreads();
     if (l == 0 && g < groups) {
         f32x4 t = part[0][gl];
 #pragma unroll
-        for (int q = 1; q < 16; ++q) t += part[q][gl];
+        for (int q = 1; q < LANES; ++q) t += part[q][gl];
         const int64_t i = g * 4;
         *reinterpret_cast<f32x4*>(C + (i / N) * ldc + (i % N)) = t;
     }
@@ -216,8 +219,11 @@ hipError_t reduce_partials(const float* partial, void* C, bool c_bf16, int64_t l
             hipLaunchKernelGGL((reduce_partials_kernel<1, bf16_t>), dim3(blocks_for(M * N)), dim3(256), 0, st, partial,
                                (bf16_t*)C, ldc, M, N, splits);
     } else {
-        if (al && N % 4 == 0 && ldc % 4 == 0 && splits >= 16 && M * N / 4 < 256 * 256)
-            hipLaunchKernelGGL(reduce_partials_wide_kernel, dim3((unsigned)ceil_div(M * N / 4, 16)), dim3(256), 0, st, partial,
+        if (al && N % 4 == 0 && ldc % 4 == 0 && splits >= 64 && M * N / 4 <= 4096)
+            hipLaunchKernelGGL(reduce_partials_wide_kernel<64>, dim3((unsigned)ceil_div(M * N / 4, 4)), dim3(256), 0, st, partial,
+                               (float*)C, ldc, M, N, splits);
+        else if (al && N % 4 == 0 && ldc % 4 == 0 && splits >= 16 && M * N / 4 < 256 * 256)
+            hipLaunchKernelGGL(reduce_partials_wide_kernel<16>, dim3((unsigned)ceil_div(M * N / 4, 16)), dim3(256), 0, st, partial,
                                (float*)C, ldc, M, N, splits);
         else if (al && N % 4 == 0 && ldc % 4 == 0)
             hipLaunchKernelGGL((reduce_partials_kernel<4, float>), dim3(blocks_for(M * N / 4)), dim3(256), 0, st, partial,
