@@ -51,6 +51,9 @@ def _load():
         lib.lrd_ref_tucker_rank.restype = c_int
         lib.lrd_ref_tucker_rank.argtypes = [c_int64, c_int64, c_int32, c_double, c_double,
                                             POINTER(c_int32), POINTER(c_int32)]
+        lib.lrd_ref_select_rank.restype = c_int32
+        lib.lrd_ref_select_rank.argtypes = [ctypes.POINTER(c_double), c_int32, c_int32, c_double, c_double, c_int32,
+                                            ctypes.POINTER(c_int32), ctypes.POINTER(c_int32)]
         lib.lrd_ref_svd_rank.restype = c_int32
         lib.lrd_ref_svd_rank.argtypes = [c_int64, c_int64, c_double]
         lib.lrd_ref_linear_fwd.restype = None
@@ -121,6 +124,18 @@ def tucker_rank(C: int, S: int, k: int, alpha: float, beta: float = 1.0):
     if rc != 0:
         raise ValueError("bad arguments")
     return int(r1.value), int(r2.value)
+
+
+def select_rank(times, r_min: int, r_max: int, t_dense: float, noise: float = 0.0, mode: int = 0):
+    """Algorithm 1's rank choice from measured times; returns (r_opt, keep_decomposed) or raises ValueError."""
+    arr = (c_double * len(times))(*[float(v) for v in times])
+    if len(times) != r_max - r_min + 1:
+        raise ValueError("times must cover r_min..r_max")
+    r_opt, keep = c_int32(0), c_int32(0)
+    rc = _load().lrd_ref_select_rank(arr, r_min, r_max, t_dense, noise, mode, ctypes.byref(r_opt), ctypes.byref(keep))
+    if rc != 0:
+        raise ValueError("invalid arguments")
+    return int(r_opt.value), bool(keep.value)
 
 
 def svd_rank(n_in: int, n_out: int, alpha: float) -> int:

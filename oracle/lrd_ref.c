@@ -126,6 +126,61 @@ int32_t lrd_ref_svd_rank(int64_t in, int64_t out, double alpha)
     return (int32_t)r;
 }
 
+/*
+ * Rank search of Algorithm 1 (Section 3.1, Rank Optimization), given the measured step times.
+ * t[i] is the step time of the layer decomposed at rank r_min + i, i = 0 .. r_max - r_min;
+ * t_dense the step time of the original layer.  The listing cannot be run as printed (it uses
+ * t(r-1) before it is measured, and indexes the 257 -> 256 drop at 257 while the rank it wants
+ * is 256), so this follows the text around it:
+ *   d(r) = t(r) - t(r-1) for r in (r_min, r_max]  -- the first derivative of step time vs rank;
+ *   mode 0 (text): going down from r_max, the first r whose d(r) exceeds `noise` and is not
+ *                  smaller than its neighbours d(r+1), d(r-1) ("first peak");
+ *   mode 1 (listing): the r with the largest d(r) over the whole range (ties: the largest r),
+ *                  accepted only if d(r) exceeds `noise`;
+ *   the rank just below that drop is the optimum, R_opt = r - 1; without such an r the estimated
+ *   rank stays, R_opt = r_max;
+ *   the decomposed layer is used iff t(R_opt) < t_dense.
+ * Returns 0, or -1 on invalid arguments (empty range, non-finite times, negative noise).
+ */
+int32_t lrd_ref_select_rank(const double* t, int32_t r_min, int32_t r_max, double t_dense, double noise,
+                            int32_t mode, int32_t* r_opt, int32_t* keep_decomposed)
+{
+    if (!t || !r_opt || !keep_decomposed || r_min < 1 || r_max < r_min || (mode != 0 && mode != 1)) return -1;
+    if (!(noise >= 0.0) || !isfinite(noise) || !isfinite(t_dense)) return -1;
+    const int32_t n = r_max - r_min + 1;
+    for (int32_t i = 0; i < n; ++i)
+        if (!isfinite(t[i])) return -1;
+    int32_t found = 0;                      /* the r of the drop, 0 if none */
+    if (mode == 0) {
+        for (int32_t r = r_max; r > r_min && !found; --r) {
+            double d = t[r - r_min] - t[r - 1 - r_min];
+            if (!(d > noise)) continue;
+            int peak = 1;
+            if (r < r_max) {
+                double up = t[r + 1 - r_min] - t[r - r_min];
+                if (d < up) peak = 0;
+            }
+            if (r - 1 > r_min) {
+                double down = t[r - 1 - r_min] - t[r - 2 - r_min];
+                if (d < down) peak = 0;
+            }
+            if (peak) found = r;
+        }
+    } else {
+        double best = 0.0;
+        for (int32_t r = r_max; r > r_min; --r) {
+            double d = t[r - r_min] - t[r - 1 - r_min];
+            if (d > noise && (!found || d > best)) {
+                best = d;
+                found = r;
+            }
+        }
+    }
+    *r_opt = found ? found - 1 : r_max;
+    *keep_decomposed = t[*r_opt - r_min] < t_dense ? 1 : 0;
+    return 0;
+}
+
 /* ------------------------------------------------------------------------------------------ */
 /* SVD-decomposed linear layer (Section 2, Fig. 1: one FC layer -> two consecutive FC layers)  */
 /* ------------------------------------------------------------------------------------------ */

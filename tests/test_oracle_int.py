@@ -1,5 +1,5 @@
 """Pins for the oracle's integer rules: rank quantization (Section 2.1), the rank formulas
-(eq. 6 / eq. 7) and the sequential-freezing schedule (Algorithm 2)."""
+(eq. 6 / eq. 7), the rank search of Algorithm 1 and the sequential-freezing schedule (Algorithm 2)."""
 import math
 
 import oracle
@@ -148,3 +148,77 @@ def test_quantize_examples_and_bounds():
     # bad arguments
     for args in ((0, 16, 0, 1, 100), (10, 0, 0, 1, 100), (10, 16, 3, 1, 100), (10, 16, 0, 5, 4)):
         assert oracle.quantize_rank(*args) < 0
+
+
+# ---------------------------------------------------------------- Algorithm 1: rank search from measured times
+def test_alg1_worked_examples():
+    for row in read_golden("alg1_rank_search.txt"):
+        mode, r_min, r_max = int(row[0]), int(row[1]), int(row[2])
+        noise, t_dense = float(row[3]), float(row[4])
+        want_r, want_keep = int(row[5]), bool(int(row[6]))
+        times = [float(x) for x in row[7:]]
+        assert oracle.select_rank(times, r_min, r_max, t_dense, noise, mode) == (want_r, want_keep), row
+
+
+def _staircase(r_min, r_max, m, slope=0.0):
+    """Step time of a kernel that pads the rank up to a multiple of m (plus an optional small slope)."""
+    return [float(-(-r // m)) + slope * r for r in range(r_min, r_max + 1)]
+
+
+def test_alg1_staircase_agrees_with_rank_quantization():
+    # On an ideal staircase the first drop below a misaligned estimated rank is the multiple of m just
+    # below it: Algorithm 1 and rounding down to a multiple (two separate routines) must agree.
+    for m in (8, 16, 32, 64):
+        for R in (m + 1, 2 * m - 1, 3 * m + 5, 309, 257):
+            if R % m == 0:
+                continue
+            for mode in (0, 1):
+                # first-peak mode may see a second drop further down; arg max gets a range holding one drop only
+                r_min = max(1, R - 2 * m) if mode == 0 else max(1, R - R % m - 3)
+                times = _staircase(r_min, R, m, slope=1e-4)
+                r_opt, keep = oracle.select_rank(times, r_min, R, 1e9, 0.01, mode)
+                assert r_opt == oracle.quantize_rank(R, m, oracle.ROUND_DOWN), (m, R, mode)
+                assert keep
+
+
+def test_alg1_invariances():
+    rng = __import__("random").Random(7)
+    for _ in range(200):
+        n = rng.randint(1, 12)
+        r_min = rng.randint(1, 40)
+        r_max = r_min + n - 1
+        times = [rng.choice((1.0, 1.25, 1.5, 2.0)) for _ in range(n)]
+        t_dense = rng.choice((0.5, 1.3, 3.0))
+        noise = rng.choice((0.0, 0.1, 0.3))
+        for mode in (0, 1):
+            base = oracle.select_rank(times, r_min, r_max, t_dense, noise, mode)
+            # a constant offset on every time (dense included) and a common positive factor change nothing
+            assert oracle.select_rank([t + 4.0 for t in times], r_min, r_max, t_dense + 4.0, noise, mode) == base
+            assert oracle.select_rank([t * 8.0 for t in times], r_min, r_max, t_dense * 8.0, noise * 8.0, mode) == base
+            r_opt, keep = base
+            assert r_min <= r_opt <= r_max
+            assert keep == (times[r_opt - r_min] < t_dense)
+            d = {r: times[r - r_min] - times[r - 1 - r_min] for r in range(r_min + 1, r_max + 1)}
+            big = [r for r in d if d[r] > noise]
+            if r_opt == r_max:
+                # nothing chosen: in arg-max mode no difference exceeds the noise; in first-peak mode none of
+                # those that do is a local maximum (impossible: the largest one always is), so none exceeds it
+                assert not big
+            else:
+                r_star = r_opt + 1
+                assert d[r_star] > noise
+                if mode == 1:
+                    assert d[r_star] == max(d.values()) and all(d[r] < d[r_star] for r in d if r > r_star)
+                else:
+                    assert d[r_star] >= d.get(r_star + 1, -math.inf) and d[r_star] >= d.get(r_star - 1, -math.inf)
+                    for r in big:            # every higher candidate is beaten by a neighbour
+                        if r > r_star:
+                            assert d[r] < d.get(r + 1, -math.inf) or d[r] < d.get(r - 1, -math.inf)
+
+
+def test_alg1_rejects_bad_arguments():
+    import pytest
+    for bad in (dict(times=[1.0, 2.0], r_min=0, r_max=1), dict(times=[1.0], r_min=3, r_max=3, noise=-1.0),
+                dict(times=[1.0, float("nan")], r_min=3, r_max=4), dict(times=[1.0], r_min=3, r_max=3, mode=2)):
+        with pytest.raises(ValueError):
+            oracle.select_rank(bad["times"], bad["r_min"], bad["r_max"], 1.0, bad.get("noise", 0.0), bad.get("mode", 0))
