@@ -358,6 +358,110 @@ def layer_tables(args, torch, lrd):
                                  "bf16, microseconds per call", conv_stages=conv, projections=lin)))
 
 
+def rank_search(args, torch, lrd):
+    """Algorithm 1 (rank optimization) run on the device: step time (forward + backward, nothing frozen)
+    of every rank from the estimated one (eq. 6 at compression alpha = 2) down to the lower bound (eq. 7,
+    alpha + 1), lrd_select_rank on the measured curve, and the aligned ranks lrd_quantize_rank would have
+    picked, for the paper's [512,512,3,3] Tucker layer (N = 128, 7 x 7) and the 4096 x 4096 linear layer
+    (16384 tokens).  Timing only; prints one JSON line."""
+    bf = torch.bfloat16
+    gen = torch.Generator(device="cuda").manual_seed(230903824 + 6)
+
+    def rnd(*shape, scale=1.0):
+        return (torch.randn(*shape, device="cuda", generator=gen) * scale).to(bf)
+
+    def empty(*shape, dt=bf):
+        return torch.empty(*shape, dtype=dt, device="cuda")
+
+    def timeit(fn, iters):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        for _ in range(iters):
+            fn()
+        e.record()
+        torch.cuda.synchronize()
+        return s.elapsed_time(e) * 1e3 / iters
+
+    def report(name, ranks, times, t_dense, extra):
+        r_min, r_max = ranks[0], ranks[-1]
+        noise = 0.03 * sorted(times)[len(times) // 2]      # differences below 3 % of the median step are jitter
+        out = dict(layer=name, r_estimated=r_max, r_min=r_min, dense_us=t_dense, noise_us=noise,
+                   t_estimated_us=times[-1], **extra)
+        for label, mode in (("first_peak", lrd.SELECT_FIRST_PEAK), ("argmax", lrd.SELECT_ARGMAX)):
+            r_opt, keep = lrd.select_rank(times, r_min, r_max, t_dense, noise, mode)
+            out[label] = dict(r_opt=r_opt, keep_decomposed=keep, t_us=times[r_opt - r_min],
+                              speedup_vs_estimated=times[-1] / times[r_opt - r_min],
+                              speedup_vs_dense=t_dense / times[r_opt - r_min])
+        out["quantize_down"] = {str(m): dict(r=lrd.quantize_rank(r_max, m, lrd.ROUND_DOWN, r_min, r_max),
+                                             t_us=times[lrd.quantize_rank(r_max, m, lrd.ROUND_DOWN, r_min, r_max) - r_min])
+                                for m in (8, 16, 32, 64)}
+        out["curve_us"] = [round(t, 1) for t in times]
+        return out
+
+    results = []
+    # --- the paper's worked example: [512,512,3,3], Tucker-2 at 2x compression
+    C, k, N, hw = 512, 3, 128, 7
+    R, _ = lrd.tucker_rank(C, C, k, 2.0, 1.0)
+    R_min, _ = lrd.tucker_rank(C, C, k, 3.0, 1.0)
+    X, dY = rnd(N, hw, hw, C), rnd(N, hw, hw, C)
+    Y, dX = empty(N, hw, hw, C), empty(N, hw, hw, C)
+    ranks = list(range(R_min, R + 1))
+    gmax = lrd.conv_geom(N, hw, hw, C, C, R, R, k, 1, 1)
+    ws = torch.empty(max(lrd.tucker_conv_workspace_bytes(lrd.conv_geom(N, hw, hw, C, C, r, r, k, 1, 1), lrd.BF16, 0)
+                         for r in ranks) + 256, dtype=torch.uint8, device="cuda")
+    times = []
+    for r in ranks:
+        g = lrd.conv_geom(N, hw, hw, C, C, r, r, k, 1, 1)
+        P1, G, P2 = rnd(r, C, scale=C ** -0.5), rnd(r, k, k, r, scale=(k * k * r) ** -0.5), rnd(C, r, scale=r ** -0.5)
+        A, B = empty(N, hw, hw, r), empty(N, hw, hw, r)
+        dP1, dG, dP2 = empty(r, C, dt=torch.float32), empty(r, k, k, r, dt=torch.float32), empty(C, r, dt=torch.float32)
+
+        def step():
+            lrd.tucker_conv_fwd(X, P1, G, P2, Y, A, B, g, ws)
+            lrd.tucker_conv_bwd(dY, X, A, B, P1, G, P2, dX, dP1, dG, dP2, 0, g, ws)
+        times.append(timeit(step, args.sweep_iters))
+    W, dW = rnd(C, k, k, C, scale=(k * k * C) ** -0.5), empty(C, k, k, C, dt=torch.float32)
+    wsd = torch.empty(lrd.dense_conv_workspace_bytes(gmax, lrd.BF16) + 256, dtype=torch.uint8, device="cuda")
+
+    def dense_step():
+        lrd.dense_conv_fwd(X, W, Y, gmax, wsd)
+        lrd.dense_conv_bwd(dY, X, W, dX, dW, gmax, wsd)
+    results.append(report("tucker [512,512,3,3], N=128, 7x7", ranks, times, timeit(dense_step, args.sweep_iters),
+                          dict(alpha=2.0)))
+    del X, dY, Y, dX, ws, wsd
+
+    # --- the 4096 x 4096 linear layer at 2x compression
+    T, d = 16384, 4096
+    R, R_min = lrd.svd_rank(d, d, 2.0), lrd.svd_rank(d, d, 3.0)
+    X, dY = rnd(T, d), rnd(T, d)
+    Y, dX = empty(T, d), empty(T, d)
+    ranks = list(range(R_min, R + 1))
+    ws = torch.empty(max(lrd.linear_workspace_bytes(T, d, d, r, lrd.BF16, 0) for r in (R, R - 1)) + 256,
+                     dtype=torch.uint8, device="cuda")
+    times = []
+    for r in ranks:
+        V, U = rnd(r, d, scale=d ** -0.5), rnd(d, r, scale=r ** -0.5)
+        H = empty(T, r)
+        dV, dU = empty(r, d, dt=torch.float32), empty(d, r, dt=torch.float32)
+
+        def step():
+            lrd.linear_fwd(X, V, U, None, Y, H, ws)
+            lrd.linear_bwd(dY, X, H, V, U, dX, dV, dU, None, 0, ws)
+        times.append(timeit(step, max(2, args.sweep_iters // 2)))
+    W, dW = rnd(d, d, scale=d ** -0.5), empty(d, d, dt=torch.float32)
+    wsd = torch.empty(lrd.dense_linear_workspace_bytes(T, d, d, lrd.BF16) + 256, dtype=torch.uint8, device="cuda")
+
+    def dense_lin():
+        lrd.dense_linear_fwd(X, W, None, Y, wsd)
+        lrd.dense_linear_bwd(dY, X, W, dX, dW, wsd)
+    results.append(report("linear 4096x4096, 16384 tokens", ranks, times, timeit(dense_lin, 5), dict(alpha=2.0)))
+    print(json.dumps(dict(metric="rank search (Algorithm 1) on measured forward + backward step times, bf16, microseconds",
+                          layers=results)))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -367,6 +471,8 @@ def main():
     ap.add_argument("--no-comparators", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
     ap.add_argument("--rank-sweep", action="store_true", help="run the rank sweep (config 3) instead of the FFN stack")
+    ap.add_argument("--rank-search", action="store_true",
+                    help="run Algorithm 1's rank search on measured step times (Tucker [512,512,3,3] and linear 4096^2) instead")
     ap.add_argument("--layer-tables", action="store_true",
                     help="time the Tucker conv stages (config 4) and the transformer projections (config 5) instead")
     ap.add_argument("--sweep-step", type=int, default=16)
@@ -395,6 +501,9 @@ def main():
         return
     if args.layer_tables:
         layer_tables(args, torch, lrd)
+        return
+    if args.rank_search:
+        rank_search(args, torch, lrd)
         return
 
     if args.calibrate_copy:

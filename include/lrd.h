@@ -110,6 +110,29 @@ lrd_status lrd_tucker_rank(int64_t C, int64_t S, int32_t k, double alpha, double
  */
 int32_t lrd_svd_rank(int64_t in, int64_t out, double alpha);
 
+/*
+ * Rank search of Algorithm 1 (Section 3.1, Rank Optimization) from measured step times.
+ *   times[i]  host array, step time of the layer decomposed at rank r_min + i, i = 0 .. r_max - r_min
+ *             (any unit; the caller measures them, e.g. forward + backward through this library);
+ *   t_dense   step time of the original layer in the same unit;
+ *   noise     differences t(r) - t(r-1) at or below this value are not drops (>= 0).
+ * The printed listing cannot run as it stands (it needs t(r-1) before measuring it and indexes the
+ * 257 -> 256 drop at 257), so the search follows the surrounding text: with d(r) = t(r) - t(r-1),
+ *   LRD_SELECT_FIRST_PEAK  going down from r_max, the first r with d(r) > noise that is not below
+ *                          its neighbours d(r+1), d(r-1)  (the text's "first peak");
+ *   LRD_SELECT_ARGMAX      the r with the largest d(r) > noise in the range, ties to the largest r
+ *                          (the listing's arg max);
+ * *r_opt = r - 1, the rank just below that drop, or r_max when there is none or when that rank is
+ * not faster than r_max itself (the algorithm looks for a more efficient rank; an estimated rank
+ * that is already aligned stays);
+ * *keep_decomposed = 1 iff t(*r_opt) < t_dense (otherwise the original layer is the faster one).
+ * Pure host function.  LRD_ERR_INVALID_ARG for NULL pointers, an empty range, r_min < 1, negative
+ * noise or non-finite times.
+ */
+enum { LRD_SELECT_FIRST_PEAK = 0, LRD_SELECT_ARGMAX = 1 };
+lrd_status lrd_select_rank(const double* times, int32_t r_min, int32_t r_max, double t_dense, double noise,
+                           int32_t mode, int32_t* r_opt, int32_t* keep_decomposed);
+
 /* ------------------------------------------------------------------------------------------
  * SVD-decomposed linear layer (Section 2, Fig. 1; freezing: Section 2.2)
  * ---------------------------------------------------------------------------------------- */

@@ -137,8 +137,9 @@ int32_t lrd_ref_svd_rank(int64_t in, int64_t out, double alpha)
  *                  smaller than its neighbours d(r+1), d(r-1) ("first peak");
  *   mode 1 (listing): the r with the largest d(r) over the whole range (ties: the largest r),
  *                  accepted only if d(r) exceeds `noise`;
- *   the rank just below that drop is the optimum, R_opt = r - 1; without such an r the estimated
- *   rank stays, R_opt = r_max;
+ *   the rank just below that drop is the optimum, R_opt = r - 1; without such an r, or when that
+ *   rank is not faster than the estimated one (an estimated rank that is already aligned), the
+ *   estimated rank stays, R_opt = r_max;
  *   the decomposed layer is used iff t(R_opt) < t_dense.
  * Returns 0, or -1 on invalid arguments (empty range, non-finite times, negative noise).
  */
@@ -177,6 +178,9 @@ int32_t lrd_ref_select_rank(const double* t, int32_t r_min, int32_t r_max, doubl
         }
     }
     *r_opt = found ? found - 1 : r_max;
+    /* the search is for a rank with "more efficient computations" than the estimated one (caption of
+     * Algorithm 1): a lower rank that is not faster than r_max only adds reconstruction error */
+    if (!(t[*r_opt - r_min] < t[r_max - r_min])) *r_opt = r_max;
     *keep_decomposed = t[*r_opt - r_min] < t_dense ? 1 : 0;
     return 0;
 }

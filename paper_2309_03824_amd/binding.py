@@ -25,7 +25,7 @@ ROUND_NEAREST, ROUND_DOWN, ROUND_UP = 0, 1, 2
 ACT_NONE, ACT_GELU = 0, 1
 
 EXPORTS = (
-    "lrd_status_string", "lrd_quantize_rank", "lrd_freeze_mask", "lrd_tucker_rank", "lrd_svd_rank",
+    "lrd_status_string", "lrd_quantize_rank", "lrd_freeze_mask", "lrd_tucker_rank", "lrd_svd_rank", "lrd_select_rank",
     "lrd_linear_workspace_bytes", "lrd_linear_fwd", "lrd_linear_bwd", "lrd_linear_fwd_act", "lrd_linear_bwd_act",
     "lrd_dense_linear_workspace_bytes", "lrd_dense_linear_fwd", "lrd_dense_linear_bwd",
     "lrd_tucker_conv_workspace_bytes", "lrd_tucker_conv_fwd", "lrd_tucker_conv_bwd",
@@ -64,6 +64,9 @@ def _load() -> ctypes.CDLL:
     lib.lrd_freeze_mask.argtypes = [c_int32, c_int64]
     lib.lrd_tucker_rank.restype = ctypes.c_int
     lib.lrd_tucker_rank.argtypes = [I64, I64, c_int32, c_double, c_double, POINTER(c_int32), POINTER(c_int32)]
+    lib.lrd_select_rank.restype = c_int32
+    lib.lrd_select_rank.argtypes = [ctypes.POINTER(c_double), c_int32, c_int32, c_double, c_double, c_int32,
+                                    ctypes.POINTER(c_int32), ctypes.POINTER(c_int32)]
     lib.lrd_svd_rank.restype = c_int32
     lib.lrd_svd_rank.argtypes = [I64, I64, c_double]
     lib.lrd_linear_workspace_bytes.restype = SZ
@@ -170,6 +173,20 @@ def svd_rank(n_in: int, n_out: int, alpha: float) -> int:
     if r < 0:
         raise LrdError(-r, "lrd_svd_rank")
     return int(r)
+
+
+SELECT_FIRST_PEAK, SELECT_ARGMAX = 0, 1
+
+
+def select_rank(times, r_min: int, r_max: int, t_dense: float, noise: float = 0.0, mode: int = SELECT_FIRST_PEAK):
+    """Algorithm 1's rank choice from measured step times: returns (r_opt, keep_decomposed)."""
+    arr = (c_double * len(times))(*[float(v) for v in times])
+    if len(times) != r_max - r_min + 1:
+        raise LrdError(1, "lrd_select_rank")
+    r_opt, keep = c_int32(0), c_int32(0)
+    _check(_lib.lrd_select_rank(arr, r_min, r_max, t_dense, noise, mode, ctypes.byref(r_opt), ctypes.byref(keep)),
+           "lrd_select_rank")
+    return int(r_opt.value), bool(keep.value)
 
 
 def set_fusion(mode: int) -> int:

@@ -1,6 +1,8 @@
 // Host-only integer rules of the library: rank quantization (Section 2.1), rank formulas
 // (eq. 6 / eq. 7) and the sequential-freezing schedule (Algorithm 2).  No device code here.
 #include <cmath>
+#include <cstddef>
+#include <vector>
 #include <cstdint>
 
 #include "lrd.h"
@@ -80,6 +82,40 @@ int32_t lrd_svd_rank(int64_t in, int64_t out, double alpha)
     const int64_t cap = in < out ? in : out;
     n = n < 1 ? 1 : (n > cap ? cap : n);
     return (int32_t)n;
+}
+
+lrd_status lrd_select_rank(const double* times, int32_t r_min, int32_t r_max, double t_dense, double noise,
+                           int32_t mode, int32_t* r_opt, int32_t* keep_decomposed)
+{
+    if (!times || !r_opt || !keep_decomposed) return LRD_ERR_INVALID_ARG;
+    if (r_min < 1 || r_max < r_min) return LRD_ERR_INVALID_ARG;
+    if (mode != LRD_SELECT_FIRST_PEAK && mode != LRD_SELECT_ARGMAX) return LRD_ERR_INVALID_ARG;
+    if (!std::isfinite(t_dense) || !std::isfinite(noise) || noise < 0.0) return LRD_ERR_INVALID_ARG;
+    const size_t count = size_t(r_max - r_min) + 1;
+    for (size_t i = 0; i < count; ++i)
+        if (!std::isfinite(times[i])) return LRD_ERR_INVALID_ARG;
+
+    // slope[i] = t(r_min + i + 1) - t(r_min + i): the increase of step time entering rank r_min + i + 1
+    std::vector<double> slope(count > 1 ? count - 1 : 0);
+    for (size_t i = 0; i + 1 < count; ++i) slope[i] = times[i + 1] - times[i];
+
+    ptrdiff_t pick = -1;   // index into slope of the chosen drop
+    if (mode == LRD_SELECT_FIRST_PEAK) {
+        for (ptrdiff_t i = (ptrdiff_t)slope.size() - 1; i >= 0; --i) {
+            if (slope[i] <= noise) continue;
+            const bool above_ok = size_t(i) + 1 >= slope.size() || slope[i] >= slope[i + 1];
+            const bool below_ok = i == 0 || slope[i] >= slope[i - 1];
+            if (above_ok && below_ok) { pick = i; break; }
+        }
+    } else {
+        for (ptrdiff_t i = (ptrdiff_t)slope.size() - 1; i >= 0; --i)
+            if (slope[i] > noise && (pick < 0 || slope[i] > slope[pick])) pick = i;
+    }
+    int32_t chosen = pick < 0 ? r_max : r_min + (int32_t)pick;   // the rank just below the drop
+    if (times[chosen - r_min] >= times[count - 1]) chosen = r_max;  // not faster than the estimated rank: keep that one
+    *r_opt = chosen;
+    *keep_decomposed = times[chosen - r_min] < t_dense ? 1 : 0;
+    return LRD_OK;
 }
 
 }  // extern "C"

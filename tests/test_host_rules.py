@@ -43,6 +43,35 @@ def test_integer_rules_match_oracle_bit_exact():
                 assert lrd.svd_rank(C, S, alpha) == oracle.svd_rank(C, S, alpha)
 
 
+def test_rank_search_matches_oracle_bit_exact():
+    import random
+    rng = random.Random(11)
+    for _ in range(3000):
+        n = rng.randint(1, 40)
+        r_min = rng.randint(1, 300)
+        r_max = r_min + n - 1
+        # staircases with jitter, plateaus and exact ties: the cases where the scan order matters
+        m = rng.choice((4, 8, 16, 32))
+        times = [float(-(-r // m)) * rng.choice((1.0, 1.0, 1.25)) + rng.choice((0.0, 0.0, 0.01, 0.5)) for r in range(r_min, r_max + 1)]
+        t_dense = rng.choice((0.5, 5.0, 50.0))
+        noise = rng.choice((0.0, 0.05, 0.3, 2.0))
+        for mode in (lrd.SELECT_FIRST_PEAK, lrd.SELECT_ARGMAX):
+            assert lrd.select_rank(times, r_min, r_max, t_dense, noise, mode) == oracle.select_rank(
+                times, r_min, r_max, t_dense, noise, mode), (times, r_min, noise, mode)
+    for row in read_golden("alg1_rank_search.txt"):
+        times = [float(x) for x in row[7:]]
+        assert lrd.select_rank(times, int(row[1]), int(row[2]), float(row[4]), float(row[3]), int(row[0])) == (
+            int(row[5]), bool(int(row[6])))
+    for bad in (([1.0, 2.0], 0, 1, 1.0, 0.0, 0), ([1.0], 3, 3, 1.0, -1.0, 0), ([1.0, float("inf")], 3, 4, 1.0, 0.0, 0),
+                ([1.0], 3, 3, 1.0, 0.0, 2), ([1.0, 2.0], 3, 3, 1.0, 0.0, 0)):
+        try:
+            lrd.select_rank(*bad)
+        except lrd.LrdError as e:
+            assert e.status == lrd.ERR_INVALID_ARG
+        else:
+            raise AssertionError(bad)
+
+
 def test_printed_examples_through_the_library():
     for row in read_golden("paper_rank_examples.txt"):
         if row[0] == "tucker_rank":

@@ -201,10 +201,15 @@ def test_alg1_invariances():
             d = {r: times[r - r_min] - times[r - 1 - r_min] for r in range(r_min + 1, r_max + 1)}
             big = [r for r in d if d[r] > noise]
             if r_opt == r_max:
-                # nothing chosen: in arg-max mode no difference exceeds the noise; in first-peak mode none of
-                # those that do is a local maximum (impossible: the largest one always is), so none exceeds it
-                assert not big
+                # nothing chosen: no difference exceeds the noise (the largest one that does is always a local
+                # maximum), or the rank below the chosen drop is not faster than the estimated rank
+                if big:
+                    r_star = max(big, key=lambda r: (d[r], r)) if mode == 1 else next(
+                        r for r in sorted(big, reverse=True)
+                        if d[r] >= d.get(r + 1, -math.inf) and d[r] >= d.get(r - 1, -math.inf))
+                    assert not times[r_star - 1 - r_min] < times[-1]
             else:
+                assert times[r_opt - r_min] < times[-1]
                 r_star = r_opt + 1
                 assert d[r_star] > noise
                 if mode == 1:
