@@ -335,6 +335,27 @@ def layer_tables(args, torch, lrd):
         stage["dense_tflops"] = 6.0 * P * k * k * C * C / ((stage["dense_fwd_us"] + stage["dense_bwd_us"]) * 1e-6) / 1e12
         conv.append(stage)
 
+    # stride-2 3x3 layers between the stages (C -> 2C, ranks C/2 and C), aligned ranks only
+    trans = []
+    for C, hw in ((64, 56), (128, 28), (256, 14)):
+        S, r1, r2, ho = 2 * C, C // 2, C, hw // 2
+        g = lrd.conv_geom(N, hw, hw, C, S, r1, r2, k, 2, 1)
+        X, dY = rnd(N, hw, hw, C), rnd(N, ho, ho, S)
+        Y, dX = empty(N, ho, ho, S), empty(N, hw, hw, C)
+        P1, G, P2 = rnd(r1, C, scale=C ** -0.5), rnd(r2, k, k, r1, scale=(k * k * r1) ** -0.5), rnd(S, r2, scale=r2 ** -0.5)
+        A, B = empty(N, hw, hw, r1), empty(N, ho, ho, r2)
+        dP1, dG, dP2 = empty(r1, C, dt=torch.float32), empty(r2, k, k, r1, dt=torch.float32), empty(S, r2, dt=torch.float32)
+        ws = torch.empty(lrd.tucker_conv_workspace_bytes(g, lrd.BF16, 0) + 256, dtype=torch.uint8, device="cuda")
+        row = dict(C=C, S=S, hw=hw, r1=r1, r2=r2, fwd_us=timeit(lambda: lrd.tucker_conv_fwd(X, P1, G, P2, Y, A, B, g, ws)))
+        for name, mask in (("core", 0b010), ("1x1", 0b101), ("none", 0)):
+            row[f"bwd_us_frozen_{name}"] = timeit(
+                lambda: lrd.tucker_conv_bwd(dY, X, A, B, P1, G, P2, dX, dP1, dG, dP2, mask, g, ws))
+        W, dW = rnd(S, k, k, C, scale=(k * k * C) ** -0.5), empty(S, k, k, C, dt=torch.float32)
+        wsd = torch.empty(lrd.dense_conv_workspace_bytes(g, lrd.BF16) + 256, dtype=torch.uint8, device="cuda")
+        row["dense_fwd_us"] = timeit(lambda: lrd.dense_conv_fwd(X, W, Y, g, wsd), 5)
+        row["dense_bwd_us"] = timeit(lambda: lrd.dense_conv_bwd(dY, X, W, dX, dW, g, wsd), 5)
+        trans.append(row)
+
     lin = []
     T, r = 8192, 256
     for n_in, n_out in ((1024, 1024), (1024, 4096), (4096, 1024)):
@@ -355,7 +376,7 @@ def layer_tables(args, torch, lrd):
         row["dense_bwd_us"] = timeit(lambda: lrd.dense_linear_bwd(dY, X, W, dX, dW, wsd), 10)
         lin.append(row)
     print(json.dumps(dict(metric="layer tables: config 4 (Tucker 3x3 stages, N = 128) and config 5 (projections, 8192 tokens, r = 256), "
-                                 "bf16, microseconds per call", conv_stages=conv, projections=lin)))
+                                 "bf16, microseconds per call", conv_stages=conv, stride2_transitions=trans, projections=lin)))
 
 
 def rank_search(args, torch, lrd):

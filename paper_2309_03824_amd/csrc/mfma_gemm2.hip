@@ -11,6 +11,8 @@
 // copied to LDS as they lie in memory and transposed by the LDS read (ds_read_b64_tr_b16) when the
 // MFMA fragments are fetched, so no layout costs a VALU instruction.  bf16 results leave through
 // LDS so that each lane stores 16 contiguous bytes of an output row.
+#include <algorithm>
+
 #include "lrd_internal.hpp"
 
 namespace lrd {
@@ -169,7 +171,8 @@ struct KmTile {
 // (tap, channel) or (image, y, x) is kept as state and advanced by BK after every load: the only
 // integer divisions are in init().
 
-// floor(t / d) for 0 <= t * d < 65536 by multiplication (d < 32 and t <= d * d + 8 here).
+// floor(t / d) for 0 <= t * d < 65536 by multiplication with ceil(65536 / d): taps by the kernel size
+// (d < 32, t <= d * d + 8) and, in the data gradient, pixel coordinates by the stride.
 __device__ __forceinline__ int small_div(int t, int magic) { return (t * magic) >> 16; }
 
 // A operand, k-contiguous.  FWD:   row = output pixel, k = (u, v, i), reads X[n, y*s+u-p, x*s+v-p, i].
@@ -184,7 +187,7 @@ struct ConvRowsTile {
     int img[CH], py[CH], px[CH];
     bool rowok[CH];
     int kc8, tap, c0;         // this thread's k of the next load, as (tap, channel); same for all its chunks
-    int ch, q_tap, r_ch, magic;
+    int ch, q_tap, r_ch, magic, magic_s;
     bool ok[DEPTH][CH];
     u32x4 st[DEPTH][CH];
 
@@ -196,6 +199,7 @@ struct ConvRowsTile {
         q_tap = BK / ch;
         r_ch = BK - q_tap * ch;
         magic = (65536 + cs.k - 1) / cs.k;
+        magic_s = (65536 + cs.stride - 1) / cs.stride;
         kc8 = (tid & 7) * 8;
         tap = (kbeg + kc8) / ch;
         c0 = (kbeg + kc8) - tap * ch;
@@ -223,16 +227,12 @@ struct ConvRowsTile {
                 int yy, xx;
                 bool inside;
                 if (DGRAD) {
-                    int ys = py[i] + cs.pad - u, xs = px[i] + cs.pad - v;
-                    if (cs.stride == 1) {
-                        yy = ys;
-                        xx = xs;
-                        inside = ys >= 0 && xs >= 0 && yy < sh && xx < sw;
-                    } else {
-                        yy = ys / cs.stride;
-                        xx = xs / cs.stride;
-                        inside = ys >= 0 && xs >= 0 && yy * cs.stride == ys && xx * cs.stride == xs && yy < sh && xx < sw;
-                    }
+                    // output pixel (ys, xs) / stride, if that is a whole number inside the output
+                    const int ys = py[i] + cs.pad - u, xs = px[i] + cs.pad - v;
+                    const int yp = max(ys, 0), xp = max(xs, 0);
+                    yy = small_div(yp, magic_s);
+                    xx = small_div(xp, magic_s);
+                    inside = ys >= 0 && xs >= 0 && yy * cs.stride == yp && xx * cs.stride == xp && yy < sh && xx < sw;
                 } else {
                     yy = py[i] * cs.stride + u - cs.pad;
                     xx = px[i] * cs.stride + v - cs.pad;
@@ -720,6 +720,8 @@ bool mfma_gemm2_supported(const MatOp& op)
             if (op.b_sk != 1 || op.b_sn % 8 != 0) return false;
         } else if (op.gather == GATHER_CONV_DGRAD) {
             akm = false; bkm = true;
+            // pixel coordinate / stride is done by multiplication, exact while coordinate * stride < 65536
+            if ((int64_t)(std::max(op.cs.H, op.cs.W) + op.cs.pad) * op.cs.stride >= 65536) return false;
         } else {
             akm = true; bkm = true;
             if (op.a_sm != 1 || op.a_sk % 8 != 0 || op.M % 8 != 0) return false;

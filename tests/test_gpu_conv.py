@@ -63,6 +63,9 @@ def test_small_tucker_all_masks(dt):
     (2, 11, 9, 20, 12, 12, 12, 5, 1, 2),     # 5x5 core
     (1, 7, 7, 8, 8, 8, 8, 3, 1, 0),          # no padding, full ranks
     (1, 3, 3, 4, 4, 2, 2, 3, 1, 1),          # image as small as the kernel
+    (2, 11, 9, 24, 16, 16, 8, 5, 1, 2),      # 5x5 core, channel counts on the 16-byte path
+    (1, 16, 16, 8, 16, 8, 8, 7, 2, 3),       # 7x7 stride 2 pad 3 (stem geometry), 16-byte path
+    (1, 20, 20, 3, 16, 3, 8, 7, 2, 3),       # the same with 3 input channels
 ])
 def test_tucker_geometries(dt, geo):
     run_tucker(*geo, dt, 0, seed=sum(geo))
@@ -89,6 +92,13 @@ def test_resnet_stage_shapes_bf16():
         for epoch in (1, 0):
             run_tucker(2, hw, hw, C, C, r, r, 3, 1, 1, "bf16", lrd.freeze_mask(lrd.KIND_TUCKER, epoch),
                        seed=50 + stage, factors=factors)
+
+
+def test_strided_stage_transitions_bf16():
+    """3x3 stride-2 layers between stages (C -> 2C, unequal ranks r1 = C/2, r2 = C), two images."""
+    for C, hw in ((64, 28), (128, 14)):
+        run_tucker(2, hw, hw, C, 2 * C, C // 2, C, 3, 2, 1, "bf16", lrd.freeze_mask(lrd.KIND_TUCKER, 1), seed=70 + C)
+        run_tucker(2, hw, hw, C, 2 * C, C // 2, C, 3, 2, 1, "bf16", 0, seed=71 + C)
 
 
 def test_tucker_rank_cliff_shapes_bf16():
