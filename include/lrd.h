@@ -277,6 +277,52 @@ enum {
 lrd_status lrd_profile_next(int32_t role, void* start_event, void* stop_event);
 
 /* ------------------------------------------------------------------------------------------
+ * One-time factorization on the device (Section 2: eq. 1, 2 truncated SVD; eq. 4 Tucker-2)
+ *
+ * Unlike the layer passes these calls SYNCHRONISE the stream (the Jacobi sweeps stop when the host
+ * reads that no pair rotated) and compute in fp64; they still allocate nothing.
+ * ---------------------------------------------------------------------------------------- */
+
+/* Workspace bytes of lrd_svd_factors for a weight [out x in] (0 on bad sizes). */
+size_t lrd_svd_factors_workspace_bytes(int64_t out, int64_t in);
+
+/*
+ * Rank-r factor pair of a layer weight (eq. 2) by one-sided Jacobi SVD (eq. 1).
+ *   W  device, fp32 [out x in] row-major (read only);
+ *   U  device, fp32 [out x r] = (left singular vectors) * sqrt(sigma);
+ *   V  device, fp32 [r x in]  = sqrt(sigma) * (right singular vectors)^T, so that U.V is the best
+ *      rank-r approximation of W and the singular values are shared evenly between the factors
+ *      (the paper leaves the split of Sigma open); components are ordered by descending sigma,
+ *      each determined up to a common sign of its U column and V row;
+ *   sigma_host   host, nullable: all min(out,in) singular values, descending (eq. 3's error is
+ *                the sum of the squares past r);
+ *   sweeps_host  host, nullable: Jacobi sweeps used.
+ * LRD_ERR_INVALID_ARG (NULL, sizes, r > min(out,in)), LRD_ERR_ALIGNMENT (16 bytes),
+ * LRD_ERR_WORKSPACE, LRD_ERR_RUNTIME (launch failure or no convergence in 60 sweeps).
+ */
+lrd_status lrd_svd_factors(const float* W, int64_t out, int64_t in, int64_t r, float* U, float* V,
+                           double* sigma_host, int32_t* sweeps_host, void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Workspace bytes of lrd_tucker2_factors for a weight [S][k][k][C] (0 on bad sizes). */
+size_t lrd_tucker2_factors_workspace_bytes(int64_t S, int64_t C, int32_t k);
+
+/*
+ * Tucker-2 factors of a convolution weight (eq. 4) by truncated higher-order SVD on the two channel
+ * modes; the spatial modes stay whole.
+ *   W   device, fp32 [S][k][k][C] (output channel, kernel row, kernel column, input channel);
+ *   P1  device, fp32 [r1 x C]: leading left singular vectors of the C-mode unfolding, as rows;
+ *   P2  device, fp32 [S x r2]: those of the S-mode unfolding, as columns;
+ *   G   device, fp32 [r2][k][k][r1]: W contracted with P1 over C and with P2 over S,
+ * in the layouts lrd_tucker_conv_fwd takes.  Basis vectors are determined up to sign (the core
+ * carries the matching signs).  r1 <= min(C, S k^2), r2 <= min(S, C k^2).
+ *   sweeps_host  host, nullable: Jacobi sweeps used by the two decompositions together.
+ * Status codes as lrd_svd_factors.
+ */
+lrd_status lrd_tucker2_factors(const float* W, int64_t S, int64_t C, int32_t k, int64_t r1, int64_t r2,
+                               float* P1, float* G, float* P2, int32_t* sweeps_host, void* ws, size_t ws_bytes,
+                               void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------
  * Glue between stacked layers (not part of the method; used by the layer-stack workloads)
  * ---------------------------------------------------------------------------------------- */
 

@@ -26,6 +26,7 @@ ACT_NONE, ACT_GELU = 0, 1
 
 EXPORTS = (
     "lrd_status_string", "lrd_quantize_rank", "lrd_freeze_mask", "lrd_tucker_rank", "lrd_svd_rank", "lrd_select_rank",
+    "lrd_svd_factors_workspace_bytes", "lrd_svd_factors", "lrd_tucker2_factors_workspace_bytes", "lrd_tucker2_factors",
     "lrd_linear_workspace_bytes", "lrd_linear_fwd", "lrd_linear_bwd", "lrd_linear_fwd_act", "lrd_linear_bwd_act",
     "lrd_dense_linear_workspace_bytes", "lrd_dense_linear_fwd", "lrd_dense_linear_bwd",
     "lrd_tucker_conv_workspace_bytes", "lrd_tucker_conv_fwd", "lrd_tucker_conv_bwd",
@@ -67,6 +68,16 @@ def _load() -> ctypes.CDLL:
     lib.lrd_select_rank.restype = c_int32
     lib.lrd_select_rank.argtypes = [ctypes.POINTER(c_double), c_int32, c_int32, c_double, c_double, c_int32,
                                     ctypes.POINTER(c_int32), ctypes.POINTER(c_int32)]
+    lib.lrd_svd_factors_workspace_bytes.restype = c_size_t
+    lib.lrd_svd_factors_workspace_bytes.argtypes = [I64, I64]
+    lib.lrd_svd_factors.restype = c_int32
+    lib.lrd_svd_factors.argtypes = [c_void_p, I64, I64, I64, c_void_p, c_void_p, ctypes.POINTER(c_double),
+                                    ctypes.POINTER(c_int32), c_void_p, c_size_t, c_void_p]
+    lib.lrd_tucker2_factors_workspace_bytes.restype = c_size_t
+    lib.lrd_tucker2_factors_workspace_bytes.argtypes = [I64, I64, c_int32]
+    lib.lrd_tucker2_factors.restype = c_int32
+    lib.lrd_tucker2_factors.argtypes = [c_void_p, I64, I64, c_int32, I64, I64, c_void_p, c_void_p, c_void_p,
+                                        ctypes.POINTER(c_int32), c_void_p, c_size_t, c_void_p]
     lib.lrd_svd_rank.restype = c_int32
     lib.lrd_svd_rank.argtypes = [I64, I64, c_double]
     lib.lrd_linear_workspace_bytes.restype = SZ
@@ -173,6 +184,35 @@ def svd_rank(n_in: int, n_out: int, alpha: float) -> int:
     if r < 0:
         raise LrdError(-r, "lrd_svd_rank")
     return int(r)
+
+
+def svd_factors_workspace_bytes(n_out: int, n_in: int) -> int:
+    return int(_lib.lrd_svd_factors_workspace_bytes(n_out, n_in))
+
+
+def svd_factors(W, r: int, U, V, ws, stream=None):
+    """Device SVD pair of W [out x in] (fp32 tensors); returns (singular values as a list, sweeps)."""
+    n_out, n_in = W.shape
+    sig = (c_double * min(n_out, n_in))()
+    sweeps = c_int32(0)
+    wp, wb = _ws(ws)
+    _check(_lib.lrd_svd_factors(_ptr(W), n_out, n_in, r, _ptr(U), _ptr(V), sig, ctypes.byref(sweeps), wp, wb,
+                                _stream(stream)), "lrd_svd_factors")
+    return list(sig), int(sweeps.value)
+
+
+def tucker2_factors_workspace_bytes(S: int, C: int, k: int) -> int:
+    return int(_lib.lrd_tucker2_factors_workspace_bytes(S, C, k))
+
+
+def tucker2_factors(W, r1: int, r2: int, P1, G, P2, ws, stream=None) -> int:
+    """Device Tucker-2 factors of W [S][k][k][C] (fp32 tensors); returns the sweeps used."""
+    S, k, _, C = W.shape
+    sweeps = c_int32(0)
+    wp, wb = _ws(ws)
+    _check(_lib.lrd_tucker2_factors(_ptr(W), S, C, k, r1, r2, _ptr(P1), _ptr(G), _ptr(P2), ctypes.byref(sweeps), wp, wb,
+                                    _stream(stream)), "lrd_tucker2_factors")
+    return int(sweeps.value)
 
 
 SELECT_FIRST_PEAK, SELECT_ARGMAX = 0, 1

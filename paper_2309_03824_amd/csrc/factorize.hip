@@ -1,0 +1,387 @@
+// One-time factorization on the device (eq. 1, 2: truncated SVD of a layer weight; eq. 4: Tucker-2
+// of a convolution weight by higher-order SVD on its two channel modes).
+//
+// The SVD is one-sided (Hestenes) Jacobi in fp64 on the ROWS of a row-major matrix M [p x q],
+// p <= q (the weight or its transpose): plane rotations make the rows mutually orthogonal, the
+// same rotations applied to Q (initially the identity) collect the left vectors.  At convergence
+// row i of M is sigma_i times a right singular vector and row i of Q the matching left vector.
+// Rows are contiguous, so every access is coalesced; the p/2 disjoint pairs of a round-robin
+// tournament step are independent and run as one launch, one workgroup per pair.  A sweep is
+// p - 1 (p even) or p (p odd) such steps; after each sweep the host reads the number of rotations
+// applied and stops at zero.  These calls therefore synchronise the stream.
+#include <algorithm>
+#include <cmath>
+#include <numeric>
+#include <vector>
+
+#include "lrd.h"
+#include "lrd_internal.hpp"
+
+namespace lrd {
+namespace {
+
+constexpr int FT = 256;                 // threads per workgroup in this file
+constexpr double JACOBI_TOL = 1e-14;    // rows count as orthogonal when |a.b| <= tol * |a| |b|
+constexpr int MAX_SWEEPS = 60;
+
+inline size_t round256(size_t b) { return (b + 255) & ~size_t(255); }
+
+// M[i][j] = transpose ? W[j][i] : W[i][j]  (W row-major with leading dimension ldw), Q = identity.
+__global__ __launch_bounds__(FT) void load_matrix_kernel(const float* __restrict__ W, int64_t ldw, bool transpose,
+                                                         double* __restrict__ M, double* __restrict__ Q, int p, int q)
+{
+    const int64_t total = (int64_t)p * q, stride = (int64_t)gridDim.x * FT;
+    for (int64_t e = (int64_t)blockIdx.x * FT + threadIdx.x; e < total; e += stride) {
+        int i = (int)(e / q), j = (int)(e - (int64_t)i * q);
+        M[e] = (double)(transpose ? W[(int64_t)j * ldw + i] : W[(int64_t)i * ldw + j]);
+    }
+    const int64_t tq = (int64_t)p * p;
+    for (int64_t e = (int64_t)blockIdx.x * FT + threadIdx.x; e < tq; e += stride) {
+        int i = (int)(e / p), j = (int)(e - (int64_t)i * p);
+        Q[e] = i == j ? 1.0 : 0.0;
+    }
+}
+
+__device__ __forceinline__ double block_sum(double v, double* scratch)
+{
+    const int tid = threadIdx.x;
+    scratch[tid] = v;
+    __syncthreads();
+#pragma unroll
+    for (int s = FT / 2; s > 0; s >>= 1) {
+        if (tid < s) scratch[tid] += scratch[tid + s];
+        __syncthreads();
+    }
+    double r = scratch[0];
+    __syncthreads();
+    return r;
+}
+
+// One step of the round-robin ordering on n players (n even; player n - 1 stays, the others
+// rotate): workgroup k pairs (n - 1, step) for k = 0 and ((step + k) mod (n - 1), (step - k) mod (n - 1))
+// otherwise.  Players >= p are byes.
+__global__ __launch_bounds__(FT) void jacobi_step_kernel(double* __restrict__ M, double* __restrict__ Q, int p, int q, int n,
+                                                         int step, double tol, unsigned int* __restrict__ rotations)
+{
+    __shared__ double scratch[FT];
+    __shared__ double cs[2];
+    const int k = blockIdx.x, m = n - 1;
+    int a, b;
+    if (k == 0) {
+        a = n - 1;
+        b = step;
+    } else {
+        a = (step + k) % m;
+        b = (step - k + m) % m;
+    }
+    if (a >= p || b >= p) return;
+    if (a > b) { int t = a; a = b; b = t; }
+    double* ra = M + (int64_t)a * q;
+    double* rb = M + (int64_t)b * q;
+    double saa = 0.0, sbb = 0.0, sab = 0.0;
+    for (int j = threadIdx.x; j < q; j += FT) {
+        double x = ra[j], y = rb[j];
+        saa += x * x;
+        sbb += y * y;
+        sab += x * y;
+    }
+    const double alpha = block_sum(saa, scratch), beta = block_sum(sbb, scratch), gamma = block_sum(sab, scratch);
+    if (threadIdx.x == 0) {
+        double c = 1.0, s = 0.0;
+        if (gamma != 0.0 && fabs(gamma) > tol * sqrt(alpha * beta)) {
+            const double zeta = (beta - alpha) / (2.0 * gamma);
+            const double t = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
+            c = 1.0 / sqrt(1.0 + t * t);
+            s = c * t;
+            atomicAdd(rotations, 1u);
+        }
+        cs[0] = c;
+        cs[1] = s;
+    }
+    __syncthreads();
+    const double c = cs[0], s = cs[1];
+    if (s == 0.0) return;
+    for (int j = threadIdx.x; j < q; j += FT) {
+        double x = ra[j], y = rb[j];
+        ra[j] = c * x - s * y;
+        rb[j] = s * x + c * y;
+    }
+    double* qa = Q + (int64_t)a * p;
+    double* qb = Q + (int64_t)b * p;
+    for (int j = threadIdx.x; j < p; j += FT) {
+        double x = qa[j], y = qb[j];
+        qa[j] = c * x - s * y;
+        qb[j] = s * x + c * y;
+    }
+}
+
+// sigma[i] = |row i of M|
+__global__ __launch_bounds__(FT) void row_norms_kernel(const double* __restrict__ M, int q, double* __restrict__ sigma)
+{
+    __shared__ double scratch[FT];
+    const double* r = M + (int64_t)blockIdx.x * q;
+    double s = 0.0;
+    for (int j = threadIdx.x; j < q; j += FT) s += r[j] * r[j];
+    s = block_sum(s, scratch);
+    if (threadIdx.x == 0) sigma[blockIdx.x] = sqrt(s);
+}
+
+// Rank-r pair with the singular values shared evenly (eq. 2).  order[j] = row holding the j-th
+// largest singular value.  wide (M = W): V[j][:] = M[row] / sqrt(sigma), U[:, j] = Q[row] * sqrt(sigma).
+// Otherwise (M = W^T) the roles of the two row spaces swap.
+__global__ __launch_bounds__(FT) void emit_pair_kernel(const double* __restrict__ M, const double* __restrict__ Q,
+                                                       const double* __restrict__ sigma, const int* __restrict__ order, int p,
+                                                       int q, int r, bool wide, float* __restrict__ U, float* __restrict__ V)
+{
+    const int j = blockIdx.x, row = order[j];
+    const double sg = sigma[row];
+    const double down = sg > 0.0 ? 1.0 / sqrt(sg) : 0.0, up = sqrt(sg);
+    const double* mr = M + (int64_t)row * q;   // sigma * vector in q-space
+    const double* qr = Q + (int64_t)row * p;   // unit vector in p-space
+    if (wide) {      // out = p, in = q
+        for (int i = threadIdx.x; i < q; i += FT) V[(int64_t)j * q + i] = (float)(mr[i] * down);
+        for (int o = threadIdx.x; o < p; o += FT) U[(int64_t)o * r + j] = (float)(qr[o] * up);
+    } else {         // in = p, out = q
+        for (int i = threadIdx.x; i < p; i += FT) V[(int64_t)j * p + i] = (float)(qr[i] * up);
+        for (int o = threadIdx.x; o < q; o += FT) U[(int64_t)o * r + j] = (float)(mr[o] * down);
+    }
+}
+
+// Leading left singular vectors as rows: B[j][:] (length p) = Q[order[j]] (M = unfolding, p <= q) or
+// (length q) = M[order[j]] / sigma (M = unfolding^T).
+__global__ __launch_bounds__(FT) void emit_basis_kernel(const double* __restrict__ M, const double* __restrict__ Q,
+                                                        const double* __restrict__ sigma, const int* __restrict__ order, int p,
+                                                        int q, bool from_q, double* __restrict__ B)
+{
+    const int j = blockIdx.x, row = order[j];
+    if (from_q) {
+        for (int i = threadIdx.x; i < p; i += FT) B[(int64_t)j * p + i] = Q[(int64_t)row * p + i];
+    } else {
+        const double sg = sigma[row], inv = sg > 0.0 ? 1.0 / sg : 0.0;
+        for (int i = threadIdx.x; i < q; i += FT) B[(int64_t)j * q + i] = M[(int64_t)row * q + i] * inv;
+    }
+}
+
+// Mode-C unfolding of W [S][kk][C]: Mc[c][(o, t)] = W[o][t][c]  (transpose = false), or its transpose.
+__global__ __launch_bounds__(FT) void unfold_c_kernel(const float* __restrict__ W, int S, int kk, int C, bool transpose,
+                                                      double* __restrict__ M, double* __restrict__ Q, int p)
+{
+    const int64_t cols = (int64_t)S * kk, total = cols * C, stride = (int64_t)gridDim.x * FT;
+    for (int64_t e = (int64_t)blockIdx.x * FT + threadIdx.x; e < total; e += stride) {
+        int64_t ot = e / C;
+        int c = (int)(e - ot * C);
+        M[transpose ? ot * C + c : (int64_t)c * cols + ot] = (double)W[e];
+    }
+    const int64_t tq = (int64_t)p * p;
+    for (int64_t e = (int64_t)blockIdx.x * FT + threadIdx.x; e < tq; e += stride) {
+        int i = (int)(e / p), j = (int)(e - (int64_t)i * p);
+        Q[e] = i == j ? 1.0 : 0.0;
+    }
+}
+
+// tmp[o][t][a] = sum_c W[o][t][c] B1[a][c]
+__global__ __launch_bounds__(FT) void core_step1_kernel(const float* __restrict__ W, const double* __restrict__ B1, int64_t rows,
+                                                        int C, int r1, double* __restrict__ tmp)
+{
+    const int64_t total = rows * r1, stride = (int64_t)gridDim.x * FT;
+    for (int64_t e = (int64_t)blockIdx.x * FT + threadIdx.x; e < total; e += stride) {
+        int64_t ot = e / r1;
+        int a = (int)(e - ot * r1);
+        double s = 0.0;
+        for (int c = 0; c < C; ++c) s += (double)W[ot * C + c] * B1[(int64_t)a * C + c];
+        tmp[e] = s;
+    }
+}
+
+// G[b][t][a] = sum_o B2[b][o] tmp[o][t][a];  also the factor outputs P1 = B1, P2[o][b] = B2[b][o].
+__global__ __launch_bounds__(FT) void core_step2_kernel(const double* __restrict__ tmp, const double* __restrict__ B1,
+                                                        const double* __restrict__ B2, int S, int kk, int C, int r1, int r2,
+                                                        float* __restrict__ G, float* __restrict__ P1, float* __restrict__ P2)
+{
+    const int64_t inner = (int64_t)kk * r1, total = (int64_t)r2 * inner, stride = (int64_t)gridDim.x * FT;
+    for (int64_t e = (int64_t)blockIdx.x * FT + threadIdx.x; e < total; e += stride) {
+        int b = (int)(e / inner);
+        int64_t ta = e - (int64_t)b * inner;
+        double s = 0.0;
+        for (int o = 0; o < S; ++o) s += B2[(int64_t)b * S + o] * tmp[(int64_t)o * inner + ta];
+        G[e] = (float)s;
+    }
+    for (int64_t e = (int64_t)blockIdx.x * FT + threadIdx.x; e < (int64_t)r1 * C; e += stride) P1[e] = (float)B1[e];
+    for (int64_t e = (int64_t)blockIdx.x * FT + threadIdx.x; e < (int64_t)S * r2; e += stride) {
+        int o = (int)(e / r2), b = (int)(e - (int64_t)o * r2);
+        P2[e] = (float)B2[(int64_t)b * S + o];
+    }
+}
+
+inline unsigned blocks_for(int64_t items)
+{
+    int64_t b = (items + FT - 1) / FT;
+    return (unsigned)std::min<int64_t>(std::max<int64_t>(b, 1), 256 * 32);
+}
+
+struct JacobiBuffers {
+    double* M;       // [p x q]
+    double* Q;       // [p x p]
+    double* sigma;   // [p]
+    int* order;      // [p]
+    unsigned int* rotations;
+};
+
+size_t jacobi_bytes(int64_t p, int64_t q)
+{
+    return round256((size_t)p * q * 8) + round256((size_t)p * p * 8) + round256((size_t)p * 8) + round256((size_t)p * 4) + 256;
+}
+
+JacobiBuffers carve_jacobi(char*& at, int64_t p, int64_t q)
+{
+    JacobiBuffers jb;
+    jb.M = (double*)at;            at += round256((size_t)p * q * 8);
+    jb.Q = (double*)at;            at += round256((size_t)p * p * 8);
+    jb.sigma = (double*)at;        at += round256((size_t)p * 8);
+    jb.order = (int*)at;           at += round256((size_t)p * 4);
+    jb.rotations = (unsigned int*)at; at += 256;
+    return jb;
+}
+
+// Sweeps until no pair rotates; then singular values to the host, descending order to the device.
+// Returns the sweeps used, or -1 on a runtime error, -2 if MAX_SWEEPS did not suffice.
+int run_jacobi(const JacobiBuffers& jb, int p, int q, std::vector<double>& sigma_host, std::vector<int>& order_host, hipStream_t st)
+{
+    const int n = (p + 1) & ~1;       // players of the tournament (one bye when p is odd)
+    int sweeps = 0;
+    bool converged = p < 2;
+    while (!converged && sweeps < MAX_SWEEPS) {
+        // the counter is cleared by a kernel-free path the stream orders with the launches
+        if (hipMemsetAsync(jb.rotations, 0, sizeof(unsigned int), st) != hipSuccess) return -1;
+        for (int step = 0; step < n - 1; ++step)
+            hipLaunchKernelGGL(jacobi_step_kernel, dim3(n / 2), dim3(FT), 0, st, jb.M, jb.Q, p, q, n, step, JACOBI_TOL, jb.rotations);
+        if (hipGetLastError() != hipSuccess) return -1;
+        unsigned int count = 0;
+        if (hipMemcpyAsync(&count, jb.rotations, sizeof count, hipMemcpyDeviceToHost, st) != hipSuccess) return -1;
+        if (hipStreamSynchronize(st) != hipSuccess) return -1;
+        ++sweeps;
+        converged = count == 0;
+    }
+    if (!converged) return -2;
+    hipLaunchKernelGGL(row_norms_kernel, dim3(p), dim3(FT), 0, st, jb.M, q, jb.sigma);
+    sigma_host.resize(p);
+    if (hipMemcpyAsync(sigma_host.data(), jb.sigma, (size_t)p * 8, hipMemcpyDeviceToHost, st) != hipSuccess) return -1;
+    if (hipStreamSynchronize(st) != hipSuccess) return -1;
+    order_host.resize(p);
+    std::iota(order_host.begin(), order_host.end(), 0);
+    std::stable_sort(order_host.begin(), order_host.end(), [&](int x, int y) { return sigma_host[x] > sigma_host[y]; });
+    if (hipMemcpyAsync(jb.order, order_host.data(), (size_t)p * 4, hipMemcpyHostToDevice, st) != hipSuccess) return -1;
+    if (hipStreamSynchronize(st) != hipSuccess) return -1;     // order_host may be reused by the caller
+    return sweeps;
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+}  // namespace lrd
+
+using namespace lrd;
+
+extern "C" {
+
+size_t lrd_svd_factors_workspace_bytes(int64_t out, int64_t in)
+{
+    if (out < 1 || in < 1 || out >= (int64_t(1) << 20) || in >= (int64_t(1) << 20)) return 0;
+    return jacobi_bytes(std::min(out, in), std::max(out, in));
+}
+
+lrd_status lrd_svd_factors(const float* W, int64_t out, int64_t in, int64_t r, float* U, float* V, double* sigma_host,
+                           int32_t* sweeps_host, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    if (!W || !U || !V || out < 1 || in < 1 || r < 1 || r > std::min(out, in)) return LRD_ERR_INVALID_ARG;
+    if (out >= (int64_t(1) << 20) || in >= (int64_t(1) << 20)) return LRD_ERR_INVALID_ARG;
+    if (!aligned16(W) || !aligned16(U) || !aligned16(V) || !aligned16(ws)) return LRD_ERR_ALIGNMENT;
+    if (!ws || ws_bytes < lrd_svd_factors_workspace_bytes(out, in)) return LRD_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const bool wide = out <= in;                 // M = W when its rows are the short side, else M = W^T
+    const int p = (int)std::min(out, in), q = (int)std::max(out, in);
+    char* at = (char*)ws;
+    JacobiBuffers jb = carve_jacobi(at, p, q);
+    hipLaunchKernelGGL(load_matrix_kernel, dim3(blocks_for((int64_t)p * q)), dim3(FT), 0, st, W, in, !wide, jb.M, jb.Q, p, q);
+    if (hipGetLastError() != hipSuccess) return LRD_ERR_RUNTIME;
+    std::vector<double> sg;
+    std::vector<int> order;
+    const int sweeps = run_jacobi(jb, p, q, sg, order, st);
+    if (sweeps < 0) return LRD_ERR_RUNTIME;
+    hipLaunchKernelGGL(emit_pair_kernel, dim3((unsigned)r), dim3(FT), 0, st, jb.M, jb.Q, jb.sigma, jb.order, p, q, (int)r, wide, U, V);
+    if (hipGetLastError() != hipSuccess || hipStreamSynchronize(st) != hipSuccess) return LRD_ERR_RUNTIME;
+    if (sigma_host)
+        for (int j = 0; j < p; ++j) sigma_host[j] = sg[order[j]];
+    if (sweeps_host) *sweeps_host = sweeps;
+    return LRD_OK;
+}
+
+size_t lrd_tucker2_factors_workspace_bytes(int64_t S, int64_t C, int32_t k)
+{
+    if (S < 1 || C < 1 || k < 1 || k > 31 || S >= (int64_t(1) << 16) || C >= (int64_t(1) << 16)) return 0;
+    const int64_t kk = (int64_t)k * k;
+    const int64_t pc = std::min(C, S * kk), qc = std::max(C, S * kk);
+    const int64_t ps = std::min(S, C * kk), qs = std::max(S, C * kk);
+    // one Jacobi problem at a time, the two bases, and the half-contracted weight
+    return std::max(jacobi_bytes(pc, qc), jacobi_bytes(ps, qs)) + round256((size_t)C * C * 8) + round256((size_t)S * S * 8) +
+           round256((size_t)S * kk * C * 8);
+}
+
+lrd_status lrd_tucker2_factors(const float* W, int64_t S, int64_t C, int32_t k, int64_t r1, int64_t r2, float* P1, float* G,
+                               float* P2, int32_t* sweeps_host, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    if (!W || !P1 || !G || !P2 || S < 1 || C < 1 || k < 1 || k > 31) return LRD_ERR_INVALID_ARG;
+    if (S >= (int64_t(1) << 16) || C >= (int64_t(1) << 16)) return LRD_ERR_INVALID_ARG;
+    const int64_t kk = (int64_t)k * k;
+    if (r1 < 1 || r2 < 1 || r1 > std::min(C, S * kk) || r2 > std::min(S, C * kk)) return LRD_ERR_INVALID_ARG;
+    if (!aligned16(W) || !aligned16(P1) || !aligned16(G) || !aligned16(P2) || !aligned16(ws)) return LRD_ERR_ALIGNMENT;
+    if (!ws || ws_bytes < lrd_tucker2_factors_workspace_bytes(S, C, k)) return LRD_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    char* base = (char*)ws;
+    const int64_t pc = std::min(C, S * kk), qc = std::max(C, S * kk);
+    const int64_t ps = std::min(S, C * kk), qs = std::max(S, C * kk);
+    char* at = base + std::max(jacobi_bytes(pc, qc), jacobi_bytes(ps, qs));
+    double* B1 = (double*)at;  at += round256((size_t)C * C * 8);     // [r1 x C] rows = basis vectors of the C mode
+    double* B2 = (double*)at;  at += round256((size_t)S * S * 8);     // [r2 x S]
+    double* tmp = (double*)at;
+    std::vector<double> sg;
+    std::vector<int> order;
+    int total_sweeps = 0;
+
+    {   // C mode: unfolding [C x S*kk]
+        char* j0 = base;
+        JacobiBuffers jb = carve_jacobi(j0, pc, qc);
+        const bool tall = C > S * kk;             // then M is the transposed unfolding
+        hipLaunchKernelGGL(unfold_c_kernel, dim3(blocks_for(S * kk * C)), dim3(FT), 0, st, W, (int)S, (int)kk, (int)C, tall, jb.M,
+                           jb.Q, (int)pc);
+        if (hipGetLastError() != hipSuccess) return LRD_ERR_RUNTIME;
+        int sw = run_jacobi(jb, (int)pc, (int)qc, sg, order, st);
+        if (sw < 0) return LRD_ERR_RUNTIME;
+        total_sweeps += sw;
+        hipLaunchKernelGGL(emit_basis_kernel, dim3((unsigned)r1), dim3(FT), 0, st, jb.M, jb.Q, jb.sigma, jb.order, (int)pc, (int)qc,
+                           !tall, B1);
+        if (hipGetLastError() != hipSuccess || hipStreamSynchronize(st) != hipSuccess) return LRD_ERR_RUNTIME;
+    }
+    {   // S mode: unfolding [S x kk*C] is W itself
+        char* j0 = base;
+        JacobiBuffers jb = carve_jacobi(j0, ps, qs);
+        const bool tall = S > C * kk;
+        hipLaunchKernelGGL(load_matrix_kernel, dim3(blocks_for(S * kk * C)), dim3(FT), 0, st, W, kk * C, tall, jb.M, jb.Q, (int)ps,
+                           (int)qs);
+        if (hipGetLastError() != hipSuccess) return LRD_ERR_RUNTIME;
+        int sw = run_jacobi(jb, (int)ps, (int)qs, sg, order, st);
+        if (sw < 0) return LRD_ERR_RUNTIME;
+        total_sweeps += sw;
+        hipLaunchKernelGGL(emit_basis_kernel, dim3((unsigned)r2), dim3(FT), 0, st, jb.M, jb.Q, jb.sigma, jb.order, (int)ps, (int)qs,
+                           !tall, B2);
+        if (hipGetLastError() != hipSuccess || hipStreamSynchronize(st) != hipSuccess) return LRD_ERR_RUNTIME;
+    }
+    hipLaunchKernelGGL(core_step1_kernel, dim3(blocks_for(S * kk * r1)), dim3(FT), 0, st, W, B1, S * kk, (int)C, (int)r1, tmp);
+    hipLaunchKernelGGL(core_step2_kernel, dim3(blocks_for(r2 * kk * r1)), dim3(FT), 0, st, tmp, B1, B2, (int)S, (int)kk, (int)C, (int)r1,
+                       (int)r2, G, P1, P2);
+    if (hipGetLastError() != hipSuccess || hipStreamSynchronize(st) != hipSuccess) return LRD_ERR_RUNTIME;
+    if (sweeps_host) *sweeps_host = total_sweeps;
+    return LRD_OK;
+}
+
+}  // extern "C"
