@@ -483,6 +483,56 @@ def rank_search(args, torch, lrd):
                           layers=results)))
 
 
+def factorize_bench(args, torch, np, si, lrd):
+    """The one-time factorization on the device (lrd_svd_factors, lrd_tucker2_factors) on the workload's
+    layer shapes, beside LAPACK on the host cores for the same matrices; prints one JSON line."""
+    import time as _t
+    rows = []
+
+    def clock(fn):
+        torch.cuda.synchronize()
+        t0 = _t.perf_counter()
+        out = fn()
+        torch.cuda.synchronize()
+        return (_t.perf_counter() - t0) * 1e3, out
+
+    for n_out, n_in, r in ((3072, 768, 192), (768, 3072, 192), (1024, 1024, 256), (4096, 4096, 1024)):
+        rng = si.rng_for(6, n_out + n_in)
+        W = si.linear_weight(n_out, n_in, rng).astype(np.float32)
+        Wd = torch.from_numpy(W).cuda()
+        U = torch.empty((n_out, r), dtype=torch.float32, device="cuda")
+        V = torch.empty((r, n_in), dtype=torch.float32, device="cuda")
+        ws = torch.empty(lrd.svd_factors_workspace_bytes(n_out, n_in) + 256, dtype=torch.uint8, device="cuda")
+        ms, (sig, sweeps) = clock(lambda: lrd.svd_factors(Wd, r, U, V, ws))
+        t0 = _t.perf_counter()
+        s_host = np.linalg.svd(W.astype(np.float64), compute_uv=True, full_matrices=False)[1]
+        host_ms = (_t.perf_counter() - t0) * 1e3
+        err = float(torch.linalg.norm(Wd.double() - U.double() @ V.double()) / torch.linalg.norm(Wd.double()))
+        best = float(np.sqrt(np.sum(s_host[r:] ** 2) / np.sum(s_host ** 2)))
+        rows.append(dict(kind="svd", out=n_out, **{"in": n_in}, r=r, gpu_ms=ms, sweeps=sweeps, host_lapack_fp64_ms=host_ms,
+                         rel_error=err, eckart_young_bound=best,
+                         sigma_max_rel_diff=float(np.max(np.abs(np.array(sig) - s_host)) / s_host[0])))
+    for S, C, k, r1 in ((64, 64, 3, 32), (256, 256, 3, 128), (512, 512, 3, 256)):
+        rng = si.rng_for(6, S + C + k)
+        W = si.conv_weight(S, C, k, rng).astype(np.float32)
+        Wd = torch.from_numpy(W).cuda()
+        P1 = torch.empty((r1, C), dtype=torch.float32, device="cuda")
+        G = torch.empty((r1, k, k, r1), dtype=torch.float32, device="cuda")
+        P2 = torch.empty((S, r1), dtype=torch.float32, device="cuda")
+        ws = torch.empty(lrd.tucker2_factors_workspace_bytes(S, C, k) + 256, dtype=torch.uint8, device="cuda")
+        ms, sweeps = clock(lambda: lrd.tucker2_factors(Wd, r1, r1, P1, G, P2, ws))
+        t0 = _t.perf_counter()
+        W64 = W.astype(np.float64)
+        np.linalg.svd(W64.transpose(3, 0, 1, 2).reshape(C, -1), full_matrices=False)
+        np.linalg.svd(W64.reshape(S, -1), full_matrices=False)
+        host_ms = (_t.perf_counter() - t0) * 1e3
+        rec = torch.einsum("ob,buva,ac->ouvc", P2.double(), G.double(), P1.double())
+        err = float(torch.linalg.norm(Wd.double() - rec) / torch.linalg.norm(Wd.double()))
+        rows.append(dict(kind="tucker2", S=S, C=C, k=k, r1=r1, r2=r1, gpu_ms=ms, sweeps=sweeps,
+                         host_lapack_fp64_ms=host_ms, rel_error=err))
+    print(json.dumps(dict(metric="one-time factorization on the device (fp64 one-sided Jacobi), milliseconds", cases=rows)))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -494,6 +544,7 @@ def main():
     ap.add_argument("--rank-sweep", action="store_true", help="run the rank sweep (config 3) instead of the FFN stack")
     ap.add_argument("--rank-search", action="store_true",
                     help="run Algorithm 1's rank search on measured step times (Tucker [512,512,3,3] and linear 4096^2) instead")
+    ap.add_argument("--factorize", action="store_true", help="time the on-device factorization (SVD pairs, Tucker-2) instead")
     ap.add_argument("--layer-tables", action="store_true",
                     help="time the Tucker conv stages (config 4) and the transformer projections (config 5) instead")
     ap.add_argument("--sweep-step", type=int, default=16)
@@ -525,6 +576,9 @@ def main():
         return
     if args.rank_search:
         rank_search(args, torch, lrd)
+        return
+    if args.factorize:
+        factorize_bench(args, torch, np, si, lrd)
         return
 
     if args.calibrate_copy:
