@@ -28,9 +28,10 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 T_TOKENS, D_MODEL, D_FF, N_BLOCKS = 8192, 768, 3072, 12
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
-# HBM bytes per launch of the reported kernel from rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000
-# (profiles/gemm2_ffn_stack_hbm_traffic.md).  Set to None whenever that kernel or its tiling changes.
-GEMM2_FWD_UP_TRAFFIC_BYTES = 66.5e6
+# HBM bytes per launch of the reported kernel, by role (2 = Y = H.U^T, 4 = dX = dH.V), from rocprofv3
+# FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (profiles/gemm2_ffn_stack_hbm_traffic.md).  Set to None whenever
+# that kernel or its tiling changes.
+GEMM2_SHORT_K_TRAFFIC_BYTES = {2: 65.9e6, 4: 67.9e6}
 
 
 def layer_flops(T, n_in, n_out, r, mask, want_dx=True):
@@ -81,19 +82,19 @@ class Stack:
         self.ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
         self.probe = None     # optional (start_event, end_event) list filled around one call class
 
-    def _probe(self):
-        """Arms the library's one-shot event probe for the next Y = H.U^T product kernel."""
+    def _probe(self, role):
+        """Arms the library's one-shot event probe for the next product kernel in this role."""
         if self.probe is not None:
             pair = (self.lrd.HipEvent(), self.lrd.HipEvent())
-            self.lrd.profile_next(self.lrd.ROLE_FWD_UP, *pair)
-            self.probe.append(pair)
+            self.lrd.profile_next(role, *pair)
+            self.probe.setdefault(role, []).append(pair)
 
     def forward(self):
         lrd = self.lrd
         for b, (l1, l2) in enumerate(self.layers):
-            self._probe()
+            self._probe(lrd.ROLE_FWD_UP)
             lrd.linear_fwd_act(self.X[b], l1["V"], l1["U"], None, self.Z[b], self.A[b], l1["H"], lrd.ACT_GELU, self.ws)
-            self._probe()
+            self._probe(lrd.ROLE_FWD_UP)
             lrd.linear_fwd(self.A[b], l2["V"], l2["U"], None, self.X[b + 1], l2["H"], self.ws)
 
     def backward(self, mask):
@@ -103,8 +104,11 @@ class Stack:
         for b in reversed(range(N_BLOCKS)):
             l1, l2 = self.layers[b]
             out = self.gX[b & 1]
+            self._probe(lrd.ROLE_DGRAD_DOWN)
             lrd.linear_bwd_act(g, self.A[b], l2["H"], l2["V"], l2["U"], self.gZ, l2["dV"], l2["dU"], None, mask,
                                self.Z[b], lrd.ACT_GELU, self.ws)
+            if b > 0:
+                self._probe(lrd.ROLE_DGRAD_DOWN)
             lrd.linear_bwd(self.gZ, self.X[b], l1["H"], l1["V"], l1["U"], out if b > 0 else None,
                            l1["dV"], l1["dU"], None, mask, self.ws)
             g = out
@@ -598,7 +602,7 @@ def main():
     for s in range(args.warmup):
         one(s)
     torch.cuda.synchronize()
-    stack.probe = []
+    stack.probe = {}
     t0 = time.perf_counter()
     for s in range(args.steps):
         one(s)
@@ -658,19 +662,31 @@ def main():
     flops = (flops_even * n_even + flops_odd * (args.steps - n_even)) / args.steps
     tflops = flops / (ms * 1e-3) / 1e12
 
-    # Dominant kernel by total time (see profiles/): the eight-wave 128x128-tile bf16 MFMA product kernel
-    # in its forward role Y = H.U^T (one launch per lrd_linear_fwd call, two shapes: out = 3072 with the
-    # GELU epilogue, which writes the pre-activation and the activation, and out = 768 without).
-    # It is bracketed by HIP events inside the timed region through lrd_profile_next.
-    # Algorithmic bytes per launch: H and U read once, Y (and the activation) written once, all bf16.
-    k_us = sum(s.elapsed_us(e) for s, e in probe) / len(probe)
+    # Dominant kernel by total time (see profiles/): the eight-wave 128x128-tile bf16 MFMA product kernel,
+    # which runs the two short-K products of a layer: Y = H.U^T in the forward (out = 3072 with the GELU
+    # epilogue, which writes the pre-activation and the activation; out = 768 without) and dX = dH.V in
+    # the backward (in = 3072 with the GELU-gradient epilogue, which reads the pre-activation; in = 768
+    # without).  Both roles are bracketed by HIP events inside the timed region through
+    # lrd_profile_next; the one with the larger total in this run is reported.
+    # Algorithmic bytes per launch, the same for both: the rank-r operand and the factor read once, the
+    # wide result written once, plus one more wide tensor (written activation / read pre-activation)
+    # under the epilogue, all bf16.
+    totals = {role: sum(s_.elapsed_us(e_) for s_, e_ in pairs) for role, pairs in probe.items()}
+    role = max(totals, key=totals.get)
+    k_us = totals[role] / len(probe[role])
     k_bytes = (2 * (T_TOKENS * rank + D_FF * rank + 2 * T_TOKENS * D_FF) +
                2 * (T_TOKENS * rank + D_MODEL * rank + T_TOKENS * D_MODEL)) / 2
+    if role == lrd.ROLE_DGRAD_DOWN:
+        # block 0's first layer needs no dX, so this role has one wide launch more than narrow ones
+        n_wide, n_narrow = N_BLOCKS, N_BLOCKS - 1
+        k_bytes = (n_wide * 2 * (T_TOKENS * rank + D_FF * rank + 2 * T_TOKENS * D_FF) +
+                   n_narrow * 2 * (T_TOKENS * rank + D_MODEL * rank + T_TOKENS * D_MODEL)) / (n_wide + n_narrow)
     achieved = k_bytes / (k_us * 1e-6) / 1e9
+    name = {lrd.ROLE_FWD_UP: "gemm2_kernel<128,128,2,4,2,false,false,bf16> as Y = H.U^T (lrd_linear_fwd / lrd_linear_fwd_act)",
+            lrd.ROLE_DGRAD_DOWN: "gemm2_kernel<128,128,2,4,2,false,true,bf16> as dX = dH.V (lrd_linear_bwd / lrd_linear_bwd_act)"}[role]
     roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved / HBM_PEAK_GBS,
-                    traffic=GEMM2_FWD_UP_TRAFFIC_BYTES,
-                    kernel="gemm2_kernel<128,128,2,4,2,false,false,bf16> as Y = H.U^T (lrd_linear_fwd / lrd_linear_fwd_act)",
-                    avg_us=k_us, launches=len(probe), bytes_per_launch=k_bytes)
+                    traffic=GEMM2_SHORT_K_TRAFFIC_BYTES[role] if GEMM2_SHORT_K_TRAFFIC_BYTES else None, kernel=name,
+                    avg_us=k_us, launches=len(probe[role]), bytes_per_launch=k_bytes)
 
     out = dict(metric="decomposed-layer fwd+bwd throughput (12-block encoder FFN stack)", value=tflops,
                unit="TFLOP/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms,
