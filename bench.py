@@ -379,8 +379,39 @@ def layer_tables(args, torch, lrd):
         row["dense_fwd_us"] = timeit(lambda: lrd.dense_linear_fwd(X, W, None, Y, wsd), 10)
         row["dense_bwd_us"] = timeit(lambda: lrd.dense_linear_bwd(dY, X, W, dX, dW, wsd), 10)
         lin.append(row)
+    # query / key / value projections of one attention block: three separate layers (their data gradients
+    # added afterwards) against the grouped call with the stacked first factor
+    G3, n_in, n_out = 3, 1024, 1024
+    X = rnd(T, n_in)
+    dY3 = rnd(G3, T, n_out)
+    V_cat, U3 = rnd(G3 * r, n_in, scale=n_in ** -0.5), rnd(G3, n_out, r, scale=r ** -0.5)
+    Y3, H3 = empty(G3, T, n_out), empty(T, G3 * r)
+    Hs = [empty(T, r) for _ in range(G3)]
+    dX, dXg = empty(T, n_in), [empty(T, n_in) for _ in range(G3)]
+    dV3, dU3 = empty(G3 * r, n_in, dt=torch.float32), empty(G3, n_out, r, dt=torch.float32)
+    ws = torch.empty(max(lrd.linear_group_workspace_bytes(T, n_in, n_out, r, G3, lrd.BF16, 0),
+                         lrd.linear_workspace_bytes(T, n_in, n_out, r, lrd.BF16, 0)) + 256, dtype=torch.uint8, device="cuda")
+
+    def separate(mask):
+        for g in range(G3):
+            lrd.linear_fwd(X, V_cat[g * r:(g + 1) * r], U3[g], None, Y3[g], Hs[g], ws)
+        for g in range(G3):
+            lrd.linear_bwd(dY3[g], X, Hs[g], V_cat[g * r:(g + 1) * r], U3[g], dXg[g], dV3[g * r:(g + 1) * r], dU3[g], None,
+                           mask, ws)
+        torch.add(dXg[0], dXg[1], out=dX)
+        dX.add_(dXg[2])
+
+    def grouped(mask):
+        lrd.linear_group_fwd(X, V_cat, U3, None, Y3, H3, ws)
+        lrd.linear_group_bwd(dY3, X, H3, V_cat, U3, dX, dV3, dU3, None, mask, ws)
+
+    qkv = dict(T=T, r=r, groups=G3, **{"in": n_in, "out": n_out})
+    for name, mask in (("V", 1), ("U", 2), ("none", 0)):
+        qkv[f"separate_us_frozen_{name}"] = timeit(lambda: separate(mask), 20)
+        qkv[f"grouped_us_frozen_{name}"] = timeit(lambda: grouped(mask), 20)
+
     print(json.dumps(dict(metric="layer tables: config 4 (Tucker 3x3 stages, N = 128) and config 5 (projections, 8192 tokens, r = 256), "
-                                 "bf16, microseconds per call", conv_stages=conv, stride2_transitions=trans, projections=lin)))
+                                 "bf16, microseconds per call", conv_stages=conv, stride2_transitions=trans, projections=lin, qkv=qkv)))
 
 
 def rank_search(args, torch, lrd):

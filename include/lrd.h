@@ -166,6 +166,27 @@ lrd_status lrd_linear_bwd(const void* dY, const void* X, const void* H, const vo
                           lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * Several decomposed layers of one shape on the same input (the query, key and value projections of
+ * an attention block, each decomposed as in Section 2).  Their first factors are stacked,
+ * V_cat [groups*r x in] (group g in rows g*r .. g*r + r - 1), so that the products with X are one
+ * product of width groups*r and the data gradients through them one product of depth groups*r; the
+ * rest is per group: U [groups][out x r], bias [groups][out] fp32 or NULL, Y and dY [groups][T x out],
+ * dU [groups][out x r] fp32, dV_cat [groups*r x in] fp32, dbias [groups][out] fp32 or NULL;
+ * H_save / H [T x groups*r] holds the groups' intermediates side by side; dX [T x in] is the sum over
+ * the groups.  freeze_mask applies to every group.  Results equal `groups` calls of lrd_linear_fwd /
+ * lrd_linear_bwd with the gradients dX added, up to summation order.  Arguments otherwise as there.
+ */
+size_t lrd_linear_group_workspace_bytes(int64_t T, int64_t in, int64_t out, int64_t r, int32_t groups,
+                                        lrd_dtype dt, uint32_t freeze_mask);
+lrd_status lrd_linear_group_fwd(const void* X, const void* V_cat, const void* U, const float* bias, void* Y,
+                                void* H_save, int64_t T, int64_t in, int64_t out, int64_t r, int32_t groups,
+                                lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream);
+lrd_status lrd_linear_group_bwd(const void* dY, const void* X, const void* H, const void* V_cat, const void* U,
+                                void* dX, float* dV_cat, float* dU, float* dbias, uint32_t freeze_mask,
+                                int64_t T, int64_t in, int64_t out, int64_t r, int32_t groups, lrd_dtype dt,
+                                void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
  * The same two calls with the activation between stacked layers folded into them (GELU, erf
  * form; not part of the paper's method, it removes two elementwise passes of a layer stack).
  *   lrd_linear_fwd_act: Y receives the pre-activation Z = H.U^T (+ bias), which the backward

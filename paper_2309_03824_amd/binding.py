@@ -26,6 +26,7 @@ ACT_NONE, ACT_GELU = 0, 1
 
 EXPORTS = (
     "lrd_status_string", "lrd_quantize_rank", "lrd_freeze_mask", "lrd_tucker_rank", "lrd_svd_rank", "lrd_select_rank",
+    "lrd_linear_group_workspace_bytes", "lrd_linear_group_fwd", "lrd_linear_group_bwd",
     "lrd_svd_factors_workspace_bytes", "lrd_svd_factors", "lrd_tucker2_factors_workspace_bytes", "lrd_tucker2_factors",
     "lrd_linear_workspace_bytes", "lrd_linear_fwd", "lrd_linear_bwd", "lrd_linear_fwd_act", "lrd_linear_bwd_act",
     "lrd_dense_linear_workspace_bytes", "lrd_dense_linear_fwd", "lrd_dense_linear_bwd",
@@ -86,6 +87,12 @@ def _load() -> ctypes.CDLL:
     lib.lrd_linear_fwd.argtypes = [P] * 6 + [I64] * 4 + [ctypes.c_int, P, SZ, P]
     lib.lrd_linear_bwd.restype = ctypes.c_int
     lib.lrd_linear_bwd.argtypes = [P] * 9 + [U32] + [I64] * 4 + [ctypes.c_int, P, SZ, P]
+    lib.lrd_linear_group_workspace_bytes.restype = SZ
+    lib.lrd_linear_group_workspace_bytes.argtypes = [I64] * 4 + [c_int32, ctypes.c_int, U32]
+    lib.lrd_linear_group_fwd.restype = ctypes.c_int
+    lib.lrd_linear_group_fwd.argtypes = [P] * 6 + [I64] * 4 + [c_int32, ctypes.c_int, P, SZ, P]
+    lib.lrd_linear_group_bwd.restype = ctypes.c_int
+    lib.lrd_linear_group_bwd.argtypes = [P] * 9 + [U32] + [I64] * 4 + [c_int32, ctypes.c_int, P, SZ, P]
     lib.lrd_linear_fwd_act.restype = ctypes.c_int
     lib.lrd_linear_fwd_act.argtypes = [P] * 7 + [c_int32] + [I64] * 4 + [ctypes.c_int, P, SZ, P]
     lib.lrd_linear_bwd_act.restype = ctypes.c_int
@@ -291,6 +298,29 @@ def linear_bwd(dY, X, H, V, U, dX, dV, dU, dbias, freeze_mask, ws=None, stream=N
     _check(_lib.lrd_linear_bwd(_ptr(dY), _ptr(X), _ptr(H), _ptr(V), _ptr(U), _ptr(dX), _ptr(dV), _ptr(dU),
                                _ptr(dbias), freeze_mask, T, n_in, n_out, r, _dt(dY), wp, wb, _stream(stream)),
            "lrd_linear_bwd")
+
+
+def linear_group_workspace_bytes(T, n_in, n_out, r, groups, dtype, freeze_mask=0) -> int:
+    return int(_lib.lrd_linear_group_workspace_bytes(T, n_in, n_out, r, groups, dtype, freeze_mask))
+
+
+def linear_group_fwd(X, V_cat, U, bias, Y, H_save, ws=None, stream=None):
+    """U [G, out, r], V_cat [G*r, in], Y [G, T, out], H_save [T, G*r] or None."""
+    T, n_in = X.shape
+    G, n_out, r = U.shape
+    assert V_cat.shape == (G * r, n_in) and Y.shape == (G, T, n_out)
+    wp, wb = _ws(ws)
+    _check(_lib.lrd_linear_group_fwd(_ptr(X), _ptr(V_cat), _ptr(U), _ptr(bias), _ptr(Y), _ptr(H_save), T, n_in, n_out, r, G,
+                                     _dt(X), wp, wb, _stream(stream)), "lrd_linear_group_fwd")
+
+
+def linear_group_bwd(dY, X, H, V_cat, U, dX, dV_cat, dU, dbias, freeze_mask, ws=None, stream=None):
+    G, T, n_out = dY.shape
+    r, n_in = U.shape[2], V_cat.shape[1]
+    wp, wb = _ws(ws)
+    _check(_lib.lrd_linear_group_bwd(_ptr(dY), _ptr(X), _ptr(H), _ptr(V_cat), _ptr(U), _ptr(dX), _ptr(dV_cat), _ptr(dU),
+                                     _ptr(dbias), freeze_mask, T, n_in, n_out, r, G, _dt(dY), wp, wb, _stream(stream)),
+           "lrd_linear_group_bwd")
 
 
 def linear_fwd_act(X, V, U, bias, Y, Y_act, H_save, act, ws=None, stream=None):

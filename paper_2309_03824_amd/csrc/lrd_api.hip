@@ -402,6 +402,132 @@ lrd_status lrd_linear_bwd_act(const void* dY, const void* X, const void* H, cons
     return LRD_OK;
 }
 
+// ------------------------------------------------------------------------------------ grouped linear
+// G decomposed layers of equal shape reading the same input (the query / key / value projections of
+// an attention block): their first factors are stacked into one [G*r x in] matrix, so the G
+// products with X become one product of width G*r and the G data gradients one product of depth
+// G*r; the second factors stay separate and address their r columns of the stacked intermediate
+// through its leading dimension.
+namespace {
+inline bool group_dims_ok(int64_t T, int64_t in, int64_t out, int64_t r, int32_t groups)
+{
+    return groups >= 1 && groups <= 64 && linear_dims_ok(T, in, out, r) && (int64_t)groups * r < (int64_t(1) << 24);
+}
+inline const char* at(const void* p, int64_t elems, lrd_dtype dt) { return (const char*)p + elems * (int64_t)esize(dt); }
+
+size_t group_partial_region(int64_t T, int64_t in, int64_t out, int64_t r, int32_t G, lrd_dtype dt, bool backward)
+{
+    const size_t h = act_partial_bytes(T, G * r, in, dt);
+    if (!backward) return h;
+    return std::max(std::max(h, act_partial_bytes(T, r, out, dt)),
+                    std::max(partial_bytes(out, r, T, dt), partial_bytes(G * r, in, T, dt)));
+}
+}  // namespace
+
+size_t lrd_linear_group_workspace_bytes(int64_t T, int64_t in, int64_t out, int64_t r, int32_t groups, lrd_dtype dt,
+                                        uint32_t freeze_mask)
+{
+    (void)freeze_mask;
+    if (!dtype_ok(dt) || !group_dims_ok(T, in, out, r, groups)) return 0;
+    const size_t act = round256((size_t)T * (size_t)groups * (size_t)r * esize(dt));
+    const size_t fwd = act + group_partial_region(T, in, out, r, groups, dt, false);
+    const size_t bwd = 2 * act + group_partial_region(T, in, out, r, groups, dt, true);
+    return std::max(fwd, bwd);
+}
+
+lrd_status lrd_linear_group_fwd(const void* X, const void* V_cat, const void* U, const float* bias, void* Y, void* H_save,
+                                int64_t T, int64_t in, int64_t out, int64_t r, int32_t groups, lrd_dtype dt, void* ws,
+                                size_t ws_bytes, void* hip_stream)
+{
+    if (!dtype_ok(dt) || !group_dims_ok(T, in, out, r, groups) || !X || !V_cat || !U || !Y) return LRD_ERR_INVALID_ARG;
+    if (!aligned16(X) || !aligned16(V_cat) || !aligned16(U) || !aligned16(Y) || !aligned16(H_save) || !aligned16(ws) ||
+        !aligned16(bias))
+        return LRD_ERR_ALIGNMENT;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int64_t gr = (int64_t)groups * r;
+    Carver cv(ws, ws_bytes);
+    void* H = H_save ? H_save : cv.take((size_t)T * gr * esize(dt));
+    const size_t region_bytes = group_partial_region(T, in, out, r, groups, dt, false);
+    void* region = region_bytes ? cv.take(region_bytes) : nullptr;
+    if (!H || !cv.ok) return LRD_ERR_WORKSPACE;
+    MatOp g1 = nt(X, in, V_cat, in, H, gr, T, gr, in, dt, false);
+    g1.role = LRD_ROLE_FWD_DOWN;
+    share_splits(g1, region, dt, SPLIT_ACT);
+    LRD_TRY(run_matop(g1, st));
+    for (int32_t g = 0; g < groups; ++g) {
+        MatOp g2 = nt(at(H, g * r, dt), gr, at(U, (int64_t)g * out * r, dt), r, (void*)at(Y, (int64_t)g * T * out, dt), out, T, out, r,
+                      dt, false);
+        g2.bias = bias ? bias + (int64_t)g * out : nullptr;
+        g2.role = LRD_ROLE_FWD_UP;
+        LRD_TRY(run_matop(g2, st));
+    }
+    return LRD_OK;
+}
+
+lrd_status lrd_linear_group_bwd(const void* dY, const void* X, const void* H, const void* V_cat, const void* U, void* dX,
+                                float* dV_cat, float* dU, float* dbias, uint32_t freeze_mask, int64_t T, int64_t in, int64_t out,
+                                int64_t r, int32_t groups, lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    if (!dtype_ok(dt) || !group_dims_ok(T, in, out, r, groups) || !dY || !V_cat || !U) return LRD_ERR_INVALID_ARG;
+    if (freeze_mask & ~uint32_t(LRD_FREEZE_L0 | LRD_FREEZE_L1)) return LRD_ERR_INVALID_ARG;
+    const bool train_v = !(freeze_mask & LRD_FREEZE_L0), train_u = !(freeze_mask & LRD_FREEZE_L1);
+    if (train_v && (!dV_cat || !X)) return LRD_ERR_INVALID_ARG;
+    if (train_u && (!dU || (!H && !X))) return LRD_ERR_INVALID_ARG;
+    if (!aligned16(dY) || !aligned16(X) || !aligned16(H) || !aligned16(V_cat) || !aligned16(U) || !aligned16(dX) ||
+        !aligned16(ws) || (train_v && !aligned16(dV_cat)) || (train_u && !aligned16(dU)) || !aligned16(dbias))
+        return LRD_ERR_ALIGNMENT;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int64_t gr = (int64_t)groups * r;
+    Carver cv(ws, ws_bytes);
+    const size_t act_bytes = (size_t)T * gr * esize(dt);
+    const bool need_dH = dX || train_v;
+    void* dH = need_dH ? cv.take(act_bytes) : nullptr;
+    void* Hre = (train_u && !H) ? cv.take(act_bytes) : nullptr;
+    const size_t region_bytes = group_partial_region(T, in, out, r, groups, dt, true);
+    void* region = region_bytes ? cv.take(region_bytes) : nullptr;
+    if (!cv.ok) return LRD_ERR_WORKSPACE;
+
+    if (need_dH) {
+        for (int32_t g = 0; g < groups; ++g) {
+            MatOp d1 = nn(at(dY, (int64_t)g * T * out, dt), out, at(U, (int64_t)g * out * r, dt), r, (void*)at(dH, g * r, dt), gr, T,
+                          r, out, dt);
+            d1.role = LRD_ROLE_DGRAD_UP;
+            share_splits(d1, region, dt, SPLIT_ACT);
+            LRD_TRY(run_matop(d1, st));
+        }
+        if (dX) {
+            MatOp d2 = nn(dH, gr, V_cat, in, dX, in, T, in, gr, dt);
+            d2.role = LRD_ROLE_DGRAD_DOWN;
+            LRD_TRY(run_matop(d2, st));
+        }
+    }
+    if (train_u) {
+        const void* Hs = H;
+        if (!H) {
+            MatOp re = nt(X, in, V_cat, in, Hre, gr, T, gr, in, dt, false);
+            share_splits(re, region, dt, SPLIT_ACT);
+            LRD_TRY(run_matop(re, st));
+            Hs = Hre;
+        }
+        for (int32_t g = 0; g < groups; ++g) {
+            MatOp wu = tn(at(dY, (int64_t)g * T * out, dt), out, at(Hs, g * r, dt), gr, dU + (int64_t)g * out * r, r, out, r, T, dt);
+            wu.role = LRD_ROLE_WGRAD_U;
+            share_splits(wu, region, dt, SPLIT_WGRAD);
+            LRD_TRY(run_matop(wu, st));
+        }
+    }
+    if (train_v) {
+        MatOp wv = tn(dH, gr, X, in, dV_cat, in, gr, in, T, dt);
+        wv.role = LRD_ROLE_WGRAD_V;
+        share_splits(wv, region, dt, SPLIT_WGRAD);
+        LRD_TRY(run_matop(wv, st));
+    }
+    if (dbias)
+        for (int32_t g = 0; g < groups; ++g)
+            LRD_TRY(column_sums(at(dY, (int64_t)g * T * out, dt), dbias + (int64_t)g * out, T, out, dt == LRD_BF16, st));
+    return LRD_OK;
+}
+
 // ------------------------------------------------------------------------------------ dense linear
 size_t lrd_dense_linear_workspace_bytes(int64_t T, int64_t in, int64_t out, lrd_dtype dt)
 {

@@ -253,3 +253,44 @@ def test_errors_reported_by_status():
     with pytest.raises(lrd.LrdError) as e:     # rank above min(in, out)
         lrd.linear_fwd(X, empty((9, 8), "f32"), empty((8, 9), "f32"), None, X.clone(), None, None)
     assert e.value.status == lrd.ERR_INVALID_ARG
+
+
+# ---------------------------------------------------------------- grouped layers on one input (Q / K / V)
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+@pytest.mark.parametrize("case", [(3, 300, 128, 96, 32), (2, 257, 64, 160, 24), (1, 128, 64, 64, 16), (3, 200, 96, 80, 12)])
+def test_grouped_linear_matches_separate_oracle_layers(dt, case):
+    G, T, n_in, n_out, r = case
+    rng = si.rng_for(5, sum(case))
+    X = si.gaussian((T, n_in), rng)
+    Us, Vs = zip(*[si.direct_factors(n_out, n_in, r, rng) for _ in range(G)])
+    U, V_cat = np.stack(Us), np.concatenate(Vs, axis=0)
+    bias = si.gaussian((G, n_out), rng).astype(np.float32)
+    dY = si.gaussian((G, T, n_out), rng)
+    ws = workspace(lrd.linear_group_workspace_bytes(T, n_in, n_out, r, G, code(dt), 0))
+    Xd, Ud, Vd, dYd = dev(X, dt), dev(U, dt), dev(V_cat, dt), dev(dY, dt)
+    bd = torch.from_numpy(bias).cuda()
+    Y, H = empty((G, T, n_out), dt), empty((T, G * r), dt)
+    lrd.linear_group_fwd(Xd, Vd, Ud, bd, Y, H, ws)
+    Xo, Uo, Vo, dYo = seen(X, dt), seen(U, dt), seen(V_cat, dt), seen(dY, dt)
+    for g in range(G):
+        Ho, Yo = oracle.linear_fwd(Xo, Vo[g * r:(g + 1) * r], Uo[g], bias[g].astype(np.float64))
+        check(host(Y[g]), Yo, dt, f"Y[{g}]")
+        check(host(H)[:, g * r:(g + 1) * r], Ho, dt, f"H[{g}]")
+    for mask in (0, 1, 2):
+        dX, dV, dU, db = empty((T, n_in), dt), f32((G * r, n_in), 7.0), f32((G, n_out, r), 7.0), f32((G, n_out))
+        lrd.linear_group_bwd(dYd, Xd, H if mask != 1 else None, Vd, Ud, dX, dV, dU, db, mask, ws)
+        dXo = np.zeros((T, n_in))
+        for g in range(G):
+            Ho, _ = oracle.linear_fwd(Xo, Vo[g * r:(g + 1) * r], Uo[g])
+            go = oracle.linear_bwd(dYo[g], Xo, Ho, Vo[g * r:(g + 1) * r], Uo[g], mask, want_dbias=True)
+            dXo += go["dX"]
+            if not mask & 2:
+                check(host(dU[g]), go["dU"], dt, f"dU[{g}]")
+            if not mask & 1:
+                check(host(dV)[g * r:(g + 1) * r], go["dV"], dt, f"dV[{g}]")
+            check(host(db[g]), go["dbias"], dt, f"dbias[{g}]")
+        check(host(dX), dXo, dt, "dX")
+        if mask & 2:
+            assert torch.all(dU == 7.0)          # frozen factors are never written
+        if mask & 1:
+            assert torch.all(dV == 7.0)
