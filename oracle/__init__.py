@@ -54,6 +54,8 @@ def _load():
         lib.lrd_ref_select_rank.restype = c_int32
         lib.lrd_ref_select_rank.argtypes = [ctypes.POINTER(c_double), c_int32, c_int32, c_double, c_double, c_int32,
                                             ctypes.POINTER(c_int32), ctypes.POINTER(c_int32)]
+        lib.lrd_ref_sgd_step.restype = None
+        lib.lrd_ref_sgd_step.argtypes = [D, D, D, c_int64, c_double, c_double, c_double]
         lib.lrd_ref_svd_rank.restype = c_int32
         lib.lrd_ref_svd_rank.argtypes = [c_int64, c_int64, c_double]
         lib.lrd_ref_linear_fwd.restype = None
@@ -136,6 +138,13 @@ def select_rank(times, r_min: int, r_max: int, t_dense: float, noise: float = 0.
     if rc != 0:
         raise ValueError("invalid arguments")
     return int(r_opt.value), bool(keep.value)
+
+
+def sgd_step(w, m, g, lr: float, momentum: float, weight_decay: float):
+    """One SGD-with-momentum step; returns the new (w, m) as fp64 arrays of the input shape."""
+    w, m, g = _in(w).copy(), _in(m).copy(), _in(g)
+    _load().lrd_ref_sgd_step(_p(w), _p(m), _p(g), w.size, lr, momentum, weight_decay)
+    return w, m
 
 
 def svd_rank(n_in: int, n_out: int, alpha: float) -> int:

@@ -490,6 +490,24 @@ void lrd_ref_tucker_bwd(const double* dY, const double* X, const double* A, cons
 }
 
 /* ------------------------------------------------------------------------------------------ */
+/* Optimizer step of the experiments (Section 4: SGD with momentum 0.9 and weight decay 1e-4)   */
+/* ------------------------------------------------------------------------------------------ */
+
+/*
+ * One step of stochastic gradient descent with momentum and weight decay on n parameters, in the
+ * usual form: g' = g + wd * w;  m <- mu * m + g';  w <- w - lr * m.  A momentum buffer that
+ * starts at zero makes the first step m = g', the common initialisation.
+ */
+void lrd_ref_sgd_step(double* w, double* m, const double* g, int64_t n, double lr, double mu, double wd)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        double gi = g[i] + wd * w[i];
+        m[i] = mu * m[i] + gi;
+        w[i] = w[i] - lr * m[i];
+    }
+}
+
+/* ------------------------------------------------------------------------------------------ */
 /* One-time factorization (eq. 1, 2, 4)                                                         */
 /* ------------------------------------------------------------------------------------------ */
 

@@ -227,3 +227,40 @@ def test_alg1_rejects_bad_arguments():
                 dict(times=[1.0, float("nan")], r_min=3, r_max=4), dict(times=[1.0], r_min=3, r_max=3, mode=2)):
         with pytest.raises(ValueError):
             oracle.select_rank(bad["times"], bad["r_min"], bad["r_max"], 1.0, bad.get("noise", 0.0), bad.get("mode", 0))
+
+
+# ---------------------------------------------------------------- optimizer step (Section 4: SGD, momentum 0.9, weight decay 1e-4)
+def test_sgd_step_matches_the_library_optimizer():
+    """Five steps against torch.optim.SGD on the CPU in fp64, momentum buffers starting at zero."""
+    import numpy as np
+    import torch
+    rng = np.random.default_rng(5)
+    for lr, mu, wd in ((1e-3, 0.9, 1e-4), (0.1, 0.0, 0.0), (0.05, 0.5, 0.1)):
+        w0 = rng.standard_normal((7, 5))
+        p = torch.nn.Parameter(torch.from_numpy(w0.copy()))
+        opt = torch.optim.SGD([p], lr=lr, momentum=mu, weight_decay=wd)
+        w, m = w0.copy(), np.zeros_like(w0)
+        for step in range(5):
+            g = rng.standard_normal(w0.shape)
+            p.grad = torch.from_numpy(g.copy())
+            opt.step()
+            w, m = oracle.sgd_step(w, m, g, lr, mu, wd)
+            assert np.max(np.abs(w - p.detach().numpy())) < 1e-14, (lr, mu, wd, step)
+
+
+def test_sgd_step_closed_forms():
+    import numpy as np
+    # constant gradient, no decay: m_k = g (1 - mu^k) / (1 - mu), w_k = w_0 - lr * sum_j m_j
+    g, mu, lr = np.array([2.0, -1.0]), 0.9, 0.01
+    w, m = np.array([1.0, 1.0]), np.zeros(2)
+    total = np.zeros(2)
+    for k in range(1, 8):
+        w, m = oracle.sgd_step(w, m, g, lr, mu, 0.0)
+        want_m = g * (1 - mu ** k) / (1 - mu)
+        total += want_m
+        assert np.allclose(m, want_m, rtol=1e-13) and np.allclose(w, 1.0 - lr * total, rtol=1e-13)
+    # zero gradient, no momentum: pure decay w_k = w_0 (1 - lr wd)^k
+    w, m = np.array([3.0]), np.zeros(1)
+    for k in range(1, 6):
+        w, m = oracle.sgd_step(w, m, np.zeros(1), 0.1, 0.0, 0.5)
+        assert np.allclose(w, 3.0 * (1 - 0.05) ** k, rtol=1e-13)
