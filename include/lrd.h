@@ -166,6 +166,35 @@ lrd_status lrd_linear_bwd(const void* dY, const void* X, const void* H, const vo
                           lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * Optimizer of the paper's experiments (Section 4: SGD, momentum 0.9, weight decay 1e-4), in the
+ * usual form g' = g + weight_decay * w;  m <- momentum * m + g';  w <- w - lr * m  (a momentum buffer
+ * that starts at zero gives the customary first step m = g').
+ *   w_master, momentum_buf  device fp32 [n], updated in place;  grad device fp32 [n];
+ *   w_copy  device, nullable: the layer's compute copy of the weights in copy_dt (bf16 or fp32),
+ *           rewritten from the new master value (may be w_master itself when copy_dt is fp32).
+ */
+typedef struct lrd_sgd { float lr, momentum, weight_decay; } lrd_sgd;
+lrd_status lrd_sgd_step(float* w_master, float* momentum_buf, const float* grad, void* w_copy, lrd_dtype copy_dt,
+                        int64_t n, const lrd_sgd* opt, void* hip_stream);
+
+/*
+ * lrd_linear_bwd_act followed by that step for every factor freeze_mask leaves trainable, in one
+ * call: the weight gradients stay in the workspace, a frozen factor costs neither a gradient nor an
+ * update (Section 2.2 carried through the optimizer).  V and U are the compute copies the layer
+ * multiplies with (dtype dt) and are rewritten; V_master / U_master and V_momentum / U_momentum are
+ * fp32 [r x in] / [out x r], required for the trainable factors, ignored for frozen ones.  The data
+ * gradient dX uses the factors as they were before the update.  Other arguments as lrd_linear_bwd_act;
+ * workspace from lrd_linear_sgd_workspace_bytes.
+ */
+size_t lrd_linear_sgd_workspace_bytes(int64_t T, int64_t in, int64_t out, int64_t r, lrd_dtype dt,
+                                      uint32_t freeze_mask);
+lrd_status lrd_linear_bwd_sgd(const void* dY, const void* X, const void* H, void* V, void* U, void* dX,
+                              float* V_master, float* U_master, float* V_momentum, float* U_momentum,
+                              float* dbias, uint32_t freeze_mask, const void* Z_in, int32_t act,
+                              const lrd_sgd* opt, int64_t T, int64_t in, int64_t out, int64_t r, lrd_dtype dt,
+                              void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
  * Several decomposed layers of one shape on the same input (the query, key and value projections of
  * an attention block, each decomposed as in Section 2).  Their first factors are stacked,
  * V_cat [groups*r x in] (group g in rows g*r .. g*r + r - 1), so that the products with X are one

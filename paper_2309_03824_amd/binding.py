@@ -26,6 +26,7 @@ ACT_NONE, ACT_GELU = 0, 1
 
 EXPORTS = (
     "lrd_status_string", "lrd_quantize_rank", "lrd_freeze_mask", "lrd_tucker_rank", "lrd_svd_rank", "lrd_select_rank",
+    "lrd_sgd_step", "lrd_linear_sgd_workspace_bytes", "lrd_linear_bwd_sgd",
     "lrd_linear_group_workspace_bytes", "lrd_linear_group_fwd", "lrd_linear_group_bwd",
     "lrd_svd_factors_workspace_bytes", "lrd_svd_factors", "lrd_tucker2_factors_workspace_bytes", "lrd_tucker2_factors",
     "lrd_linear_workspace_bytes", "lrd_linear_fwd", "lrd_linear_bwd", "lrd_linear_fwd_act", "lrd_linear_bwd_act",
@@ -40,6 +41,10 @@ class LrdError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = int(status)
         super().__init__(f"{where}: {status_string(status)}")
+
+
+class Sgd(Structure):
+    _fields_ = [("lr", ctypes.c_float), ("momentum", ctypes.c_float), ("weight_decay", ctypes.c_float)]
 
 
 class ConvGeom(Structure):
@@ -87,6 +92,12 @@ def _load() -> ctypes.CDLL:
     lib.lrd_linear_fwd.argtypes = [P] * 6 + [I64] * 4 + [ctypes.c_int, P, SZ, P]
     lib.lrd_linear_bwd.restype = ctypes.c_int
     lib.lrd_linear_bwd.argtypes = [P] * 9 + [U32] + [I64] * 4 + [ctypes.c_int, P, SZ, P]
+    lib.lrd_sgd_step.restype = ctypes.c_int
+    lib.lrd_sgd_step.argtypes = [P, P, P, P, ctypes.c_int, I64, ctypes.POINTER(Sgd), P]
+    lib.lrd_linear_sgd_workspace_bytes.restype = SZ
+    lib.lrd_linear_sgd_workspace_bytes.argtypes = [I64] * 4 + [ctypes.c_int, U32]
+    lib.lrd_linear_bwd_sgd.restype = ctypes.c_int
+    lib.lrd_linear_bwd_sgd.argtypes = [P] * 11 + [U32, P, c_int32, ctypes.POINTER(Sgd)] + [I64] * 4 + [ctypes.c_int, P, SZ, P]
     lib.lrd_linear_group_workspace_bytes.restype = SZ
     lib.lrd_linear_group_workspace_bytes.argtypes = [I64] * 4 + [c_int32, ctypes.c_int, U32]
     lib.lrd_linear_group_fwd.restype = ctypes.c_int
@@ -298,6 +309,26 @@ def linear_bwd(dY, X, H, V, U, dX, dV, dU, dbias, freeze_mask, ws=None, stream=N
     _check(_lib.lrd_linear_bwd(_ptr(dY), _ptr(X), _ptr(H), _ptr(V), _ptr(U), _ptr(dX), _ptr(dV), _ptr(dU),
                                _ptr(dbias), freeze_mask, T, n_in, n_out, r, _dt(dY), wp, wb, _stream(stream)),
            "lrd_linear_bwd")
+
+
+def sgd_step(w_master, momentum_buf, grad, w_copy, opt: "Sgd", stream=None):
+    _check(_lib.lrd_sgd_step(_ptr(w_master), _ptr(momentum_buf), _ptr(grad), _ptr(w_copy),
+                             _dt(w_copy) if w_copy is not None else F32, w_master.numel(), ctypes.byref(opt), _stream(stream)),
+           "lrd_sgd_step")
+
+
+def linear_sgd_workspace_bytes(T, n_in, n_out, r, dtype, freeze_mask=0) -> int:
+    return int(_lib.lrd_linear_sgd_workspace_bytes(T, n_in, n_out, r, dtype, freeze_mask))
+
+
+def linear_bwd_sgd(dY, X, H, V, U, dX, V_master, U_master, V_mom, U_mom, dbias, freeze_mask, Z_in, act, opt: "Sgd",
+                   ws=None, stream=None):
+    T, n_out = dY.shape
+    r, n_in = V.shape
+    wp, wb = _ws(ws)
+    _check(_lib.lrd_linear_bwd_sgd(_ptr(dY), _ptr(X), _ptr(H), _ptr(V), _ptr(U), _ptr(dX), _ptr(V_master), _ptr(U_master),
+                                   _ptr(V_mom), _ptr(U_mom), _ptr(dbias), freeze_mask, _ptr(Z_in), act, ctypes.byref(opt),
+                                   T, n_in, n_out, r, _dt(dY), wp, wb, _stream(stream)), "lrd_linear_bwd_sgd")
 
 
 def linear_group_workspace_bytes(T, n_in, n_out, r, groups, dtype, freeze_mask=0) -> int:

@@ -157,6 +157,25 @@ __global__ __launch_bounds__(256) void copy2d_kernel(const T* __restrict__ src, 
     }
 }
 
+// w <- w - lr * (m <- mu * m + (g + wd * w)) on fp32 master weights; the compute copy (bf16 or fp32,
+// optional) is refreshed from the new master value.
+__global__ __launch_bounds__(256) void sgd_step_kernel(float* __restrict__ w, float* __restrict__ m, const float* __restrict__ g,
+                                                       void* copy, bool copy_bf16, int64_t n, float lr, float mu, float wd)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const float wi = w[i];
+        const float mi = fmaf(mu, m[i], fmaf(wd, wi, g[i]));
+        const float wn = fmaf(-lr, mi, wi);
+        m[i] = mi;
+        w[i] = wn;
+        if (copy) {
+            if (copy_bf16) reinterpret_cast<bf16_t*>(copy)[i] = (bf16_t)wn;
+            else reinterpret_cast<float*>(copy)[i] = wn;
+        }
+    }
+}
+
 inline unsigned blocks_for(int64_t items)
 {
     int64_t b = ceil_div(items, 256);
@@ -203,6 +222,14 @@ hipError_t copy2d(const void* src, int64_t ld_src, int64_t rows_src, int64_t col
     else
         hipLaunchKernelGGL(copy2d_kernel<float>, grid, dim3(256), 0, st, (const float*)src, ld_src, rows_src, cols_src,
                            (float*)dst, ld_dst, rows_dst, cols_dst);
+    return hipGetLastError();
+}
+
+hipError_t sgd_step(float* w, float* m, const float* g, void* copy, bool copy_bf16, int64_t n, float lr, float mu, float wd,
+                    hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(sgd_step_kernel, dim3(blocks_for(n)), dim3(256), 0, st, w, m, g, copy, copy_bf16, n, lr, mu, wd);
     return hipGetLastError();
 }
 

@@ -402,6 +402,51 @@ lrd_status lrd_linear_bwd_act(const void* dY, const void* X, const void* H, cons
     return LRD_OK;
 }
 
+// ------------------------------------------------------------------------------------ optimizer
+lrd_status lrd_sgd_step(float* w_master, float* momentum_buf, const float* grad, void* w_copy, lrd_dtype copy_dt, int64_t n,
+                        const lrd_sgd* opt, void* hip_stream)
+{
+    if (!w_master || !momentum_buf || !grad || !opt || n < 0 || !dtype_ok(copy_dt)) return LRD_ERR_INVALID_ARG;
+    if (!(opt->lr >= 0.f) || !(opt->momentum >= 0.f) || !(opt->weight_decay >= 0.f)) return LRD_ERR_INVALID_ARG;
+    LRD_TRY(sgd_step(w_master, momentum_buf, grad, w_copy, copy_dt == LRD_BF16, n, opt->lr, opt->momentum, opt->weight_decay,
+                     (hipStream_t)hip_stream));
+    return LRD_OK;
+}
+
+size_t lrd_linear_sgd_workspace_bytes(int64_t T, int64_t in, int64_t out, int64_t r, lrd_dtype dt, uint32_t freeze_mask)
+{
+    const size_t base = lrd_linear_workspace_bytes(T, in, out, r, dt, freeze_mask);
+    if (!dtype_ok(dt) || !linear_dims_ok(T, in, out, r)) return 0;
+    return base + round256((size_t)out * r * 4) + round256((size_t)r * in * 4);
+}
+
+lrd_status lrd_linear_bwd_sgd(const void* dY, const void* X, const void* H, void* V, void* U, void* dX, float* V_master,
+                              float* U_master, float* V_momentum, float* U_momentum, float* dbias, uint32_t freeze_mask,
+                              const void* Z_in, int32_t act, const lrd_sgd* opt, int64_t T, int64_t in, int64_t out, int64_t r,
+                              lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    if (!dtype_ok(dt) || !linear_dims_ok(T, in, out, r) || !opt) return LRD_ERR_INVALID_ARG;
+    if (freeze_mask & ~uint32_t(LRD_FREEZE_L0 | LRD_FREEZE_L1)) return LRD_ERR_INVALID_ARG;
+    if (!(opt->lr >= 0.f) || !(opt->momentum >= 0.f) || !(opt->weight_decay >= 0.f)) return LRD_ERR_INVALID_ARG;
+    const bool train_v = !(freeze_mask & LRD_FREEZE_L0), train_u = !(freeze_mask & LRD_FREEZE_L1);
+    if (train_v && (!V_master || !V_momentum)) return LRD_ERR_INVALID_ARG;
+    if (train_u && (!U_master || !U_momentum)) return LRD_ERR_INVALID_ARG;
+    if (!aligned16(ws)) return LRD_ERR_ALIGNMENT;
+    // the gradients of the trainable factors live in the workspace and never reach the caller
+    Carver cv(ws, ws_bytes);
+    float* dU = train_u ? (float*)cv.take((size_t)out * r * 4) : nullptr;
+    float* dV = train_v ? (float*)cv.take((size_t)r * in * 4) : nullptr;
+    if (!cv.ok) return LRD_ERR_WORKSPACE;
+    lrd_status rc = lrd_linear_bwd_act(dY, X, H, V, U, dX, dV, dU, dbias, freeze_mask, Z_in, act, T, in, out, r, dt,
+                                       (char*)ws + cv.used, ws_bytes - cv.used, hip_stream);
+    if (rc != LRD_OK) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    // the data gradients above read V and U; the stream orders the updates after them
+    if (train_u) LRD_TRY(sgd_step(U_master, U_momentum, dU, U, dt == LRD_BF16, out * r, opt->lr, opt->momentum, opt->weight_decay, st));
+    if (train_v) LRD_TRY(sgd_step(V_master, V_momentum, dV, V, dt == LRD_BF16, r * in, opt->lr, opt->momentum, opt->weight_decay, st));
+    return LRD_OK;
+}
+
 // ------------------------------------------------------------------------------------ grouped linear
 // G decomposed layers of equal shape reading the same input (the query / key / value projections of
 // an attention block): their first factors are stacked into one [G*r x in] matrix, so the G

@@ -85,6 +85,8 @@ hipError_t column_sums(const void* dY, float* out, int64_t T, int64_t n, bool bf
 // Zero-padding / cropping copy of a row-major matrix (elem_bytes 2 or 4).
 hipError_t copy2d(const void* src, int64_t ld_src, int64_t rows_src, int64_t cols_src, void* dst, int64_t ld_dst,
                   int64_t rows_dst, int64_t cols_dst, int elem_bytes, hipStream_t st);
+hipError_t sgd_step(float* w, float* m, const float* g, void* copy, bool copy_bf16, int64_t n, float lr, float mu, float wd,
+                    hipStream_t st);
 // C = sum over split-K slices of partial[z][M][N], ascending z; C is fp32 or (c_bf16) bf16.
 hipError_t reduce_partials(const float* partial, void* C, bool c_bf16, int64_t ldc, int64_t M, int64_t N,
                            int splits, hipStream_t st);

@@ -294,3 +294,66 @@ def test_grouped_linear_matches_separate_oracle_layers(dt, case):
             assert torch.all(dU == 7.0)          # frozen factors are never written
         if mask & 1:
             assert torch.all(dV == 7.0)
+
+
+# ---------------------------------------------------------------- backward + optimizer step in one call
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_backward_with_sgd_update(dt):
+    T, n_in, n_out, r = 384, 96, 160, 32
+    rng = si.rng_for(5, 900)
+    X, dY = si.gaussian((T, n_in), rng), si.gaussian((T, n_out), rng)
+    U0, V0 = si.direct_factors(n_out, n_in, r, rng)
+    opt = lrd.Sgd(0.05, 0.9, 1e-4)
+    lr, mu, wd = float(opt.lr), float(opt.momentum), float(opt.weight_decay)
+    Um, Vm = torch.from_numpy(U0.astype(np.float32)).cuda(), torch.from_numpy(V0.astype(np.float32)).cuda()
+    Uc, Vc = dev(host(Um), dt), dev(host(Vm), dt)
+    mU, mV = f32((n_out, r), 0.0), f32((r, n_in), 0.0)
+    Xd, dYd = dev(X, dt), dev(dY, dt)
+    H, Y, dX = empty((T, r), dt), empty((T, n_out), dt), empty((T, n_in), dt)
+    ws = workspace(lrd.linear_sgd_workspace_bytes(T, n_in, n_out, r, code(dt), 0))
+    Xo, dYo = seen(X, dt), seen(dY, dt)
+    # oracle state: masters in fp64 (they hold fp32 values), momenta zero
+    Uo, Vo, mUo, mVo = host(Um), host(Vm), np.zeros((n_out, r)), np.zeros((r, n_in))
+    for step in range(4):
+        mask = lrd.freeze_mask(lrd.KIND_SVD, step)
+        lrd.linear_fwd(Xd, Vc, Uc, None, Y, H, ws)
+        before = [t.clone() for t in (Um, Vm, mU, mV, Uc, Vc)]
+        Uc_o, Vc_o = host(Uc), host(Vc)              # the values the layer multiplies with in this step
+        lrd.linear_bwd_sgd(dYd, Xd, H, Vc, Uc, dX, Vm, Um, mV, mU, None, mask, None, lrd.ACT_NONE, opt, ws)
+        Ho, _ = oracle.linear_fwd(Xo, Vc_o, Uc_o)
+        go = oracle.linear_bwd(dYo, Xo, Ho, Vc_o, Uc_o, mask)
+        check(host(dX), go["dX"], dt, "dX")
+        if mask & lrd.FREEZE_L1:                                     # U frozen: nothing of U moves
+            for a, b in ((Um, before[0]), (mU, before[2]), (Uc, before[4])):
+                assert torch.equal(a, b)
+        else:
+            Uo, mUo = oracle.sgd_step(Uo, mUo, go["dU"], lr, mu, wd)
+            check(host(mU), mUo, dt, "momentum U")
+            assert rel_err((host(Um) - host(before[0])) / lr, (Uo - host(before[0])) / lr) <= TOL[dt]
+            assert torch.equal(Uc, Um.to(Uc.dtype))                  # compute copy = rounded master
+        if mask & lrd.FREEZE_L0:
+            for a, b in ((Vm, before[1]), (mV, before[3]), (Vc, before[5])):
+                assert torch.equal(a, b)
+        else:
+            Vo, mVo = oracle.sgd_step(Vo, mVo, go["dV"], lr, mu, wd)
+            check(host(mV), mVo, dt, "momentum V")
+            assert rel_err((host(Vm) - host(before[1])) / lr, (Vo - host(before[1])) / lr) <= TOL[dt]
+            assert torch.equal(Vc, Vm.to(Vc.dtype))
+        # keep the oracle's masters on the device's values so that steps stay comparable one by one
+        Uo, Vo, mUo, mVo = host(Um), host(Vm), host(mU), host(mV)
+
+
+def test_sgd_step_alone():
+    n = 1000
+    rng = si.rng_for(5, 901)
+    w, g = si.gaussian((n,), rng).astype(np.float32), si.gaussian((n,), rng).astype(np.float32)
+    wd_, md_, gd_ = torch.from_numpy(w.copy()).cuda(), f32((n,), 0.0), torch.from_numpy(g).cuda()
+    copy = empty((n,), "bf16")
+    opt = lrd.Sgd(0.01, 0.9, 1e-4)
+    wo, mo = w.astype(np.float64), np.zeros(n)
+    for _ in range(3):
+        lrd.sgd_step(wd_, md_, gd_, copy, opt)
+        wo, mo = oracle.sgd_step(wo, mo, g, float(opt.lr), float(opt.momentum), float(opt.weight_decay))
+    assert np.max(np.abs(host(wd_) - wo)) <= 1e-6 * np.max(np.abs(wo))
+    assert np.max(np.abs(host(md_) - mo)) <= 1e-6 * np.max(np.abs(mo))
+    assert torch.equal(copy, wd_.to(torch.bfloat16))
