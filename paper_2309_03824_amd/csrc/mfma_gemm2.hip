@@ -5,12 +5,14 @@
 //   weight gradient (fp32 out)  C = A^T . B          A [K x M], B [K x N]   (both k-major), split-K
 //
 // Main loop: straight-line code, no data-dependent branches.  Every thread owns fixed 16-byte
-// chunks of the operand tiles; out-of-range rows / k are handled by clamping the ADDRESS (so the
-// load is always legal) and zeroing the VALUE when it is written to LDS, which keeps the loads
-// free of consumers and lets them stay in flight across DEPTH K-steps.  K-major operands are
-// copied to LDS as they lie in memory and transposed by the LDS read (ds_read_b64_tr_b16) when the
-// MFMA fragments are fetched, so no layout costs a VALU instruction.  bf16 results leave through
-// LDS so that each lane stores 16 contiguous bytes of an output row.
+// chunks of the operand tiles.  Plain operands are read with buffer loads whose range check returns
+// zeros outside the operand (rows or columns that do not exist get an offset no descriptor admits);
+// convolution gathers clamp the ADDRESS (so the load is always legal) and zero the VALUE when it is
+// written to LDS.  Either way the loads have no consumers until the LDS hand-off and stay in flight
+// across DEPTH K-steps; long reductions run a branch-free steady-state loop, the last steps a drain
+// loop.  K-major operands are copied to LDS as they lie in memory and transposed by the LDS read
+// (ds_read_b64_tr_b16) when the MFMA fragments are fetched, so no layout costs a VALU instruction.
+// bf16 results leave through LDS so that each lane stores 16 contiguous bytes of an output row.
 #include <algorithm>
 
 #include "lrd_internal.hpp"
