@@ -80,12 +80,13 @@ class Stack:
         nbytes = max(lrd.linear_workspace_bytes(T, D_MODEL, D_FF, rank, lrd.BF16, 0),
                      lrd.linear_workspace_bytes(T, D_FF, D_MODEL, rank, lrd.BF16, 0))
         self.ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
-        self.probe = None     # optional (start_event, end_event) list filled around one call class
+        self.probe = None     # optional {role: [(start_event, end_event), ...]} filled around the probed calls
+        self.event_pool = []  # events created ahead of the timed region
 
     def _probe(self, role):
         """Arms the library's one-shot event probe for the next product kernel in this role."""
         if self.probe is not None:
-            pair = (self.lrd.HipEvent(), self.lrd.HipEvent())
+            pair = self.event_pool.pop() if self.event_pool else (self.lrd.HipEvent(), self.lrd.HipEvent())
             self.lrd.profile_next(role, *pair)
             self.probe.setdefault(role, []).append(pair)
 
@@ -633,6 +634,7 @@ def main():
     for s in range(args.warmup):
         one(s)
     torch.cuda.synchronize()
+    stack.event_pool = [(lrd.HipEvent(), lrd.HipEvent()) for _ in range(args.steps * 4 * N_BLOCKS)]
     stack.probe = {}
     t0 = time.perf_counter()
     for s in range(args.steps):
