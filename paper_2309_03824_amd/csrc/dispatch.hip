@@ -87,7 +87,8 @@ hipError_t run_matop(const MatOp& op_in, hipStream_t st)
     if (probed) (void)hipEventRecord(ev0, st);
     hipError_t e;
     bool epilogue_done = true;
-    if (mfma_gemm2_supported(op)) e = mfma_gemm2(op, st);
+    if (conv_direct_supported(op)) e = conv_direct(op, st);
+    else if (mfma_gemm2_supported(op)) e = mfma_gemm2(op, st);
     else {
         epilogue_done = op.epilogue == EPI_NONE;
         if (mfma_matop_supported(op)) e = mfma_matop(op, st);

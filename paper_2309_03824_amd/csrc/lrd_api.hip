@@ -661,6 +661,7 @@ size_t lrd_tucker_conv_workspace_bytes(const lrd_conv_geom* g, lrd_dtype dt, uin
     size_t kk = (size_t)g->k * g->k;
     size_t part = std::max(std::max(partial_bytes(g->S, g->r2, pout, dt), partial_bytes(g->r2, kk * g->r1, pout, dt)),
                            partial_bytes(g->r1, g->C, pin, dt));
+    part = std::max(part, round256(conv_direct_wgrad_bytes(cs, dt == LRD_BF16)));
     // forward: A and B when not side-stored; backward: dA, dB, recomputed A and B, partials
     return 2 * (a + b) + part;
 }
@@ -791,10 +792,15 @@ lrd_status lrd_tucker_conv_bwd(const void* dY, const void* X, const void* A, con
     // one partial buffer, sized for the largest of the three products, used by them in turn
     shared_bytes = std::max(std::max(t2 ? partial_bytes(S, r2, pout, dt) : 0, tg ? partial_bytes(r2, kk * r1, pout, dt) : 0),
                             t1 ? partial_bytes(r1, C, pin, dt) : 0);
+    if (tg) shared_bytes = std::max(shared_bytes, round256(conv_direct_wgrad_bytes(cs, dt == LRD_BF16)));
     if (shared_bytes) shared_partial = (float*)cv.take(shared_bytes);
     if (!cv.ok) return LRD_ERR_WORKSPACE;
     if (t2) splits_for(w2);
-    if (tg) splits_for(wg);
+    if (tg) {
+        splits_for(wg);
+        wg.scratch = shared_partial;
+        wg.scratch_bytes = shared_bytes;
+    }
     if (t1) splits_for(w1);
 
     if (need_dB) LRD_TRY(run_matop(nn(dY, S, P2, r2, dB, r2, pout, r2, S, dt), st));
@@ -823,7 +829,8 @@ size_t lrd_dense_conv_workspace_bytes(const lrd_conv_geom* g, lrd_dtype dt)
 {
     if (!dtype_ok(dt) || !geom_ok(g, false)) return 0;
     ConvShape cs = core_shape(*g, g->C, g->S);
-    return partial_bytes(g->S, (int64_t)g->k * g->k * g->C, g->N * (int64_t)cs.Ho * cs.Wo, dt);
+    return std::max(partial_bytes(g->S, (int64_t)g->k * g->k * g->C, g->N * (int64_t)cs.Ho * cs.Wo, dt),
+                    round256(conv_direct_wgrad_bytes(cs, dt == LRD_BF16)));
 }
 
 lrd_status lrd_dense_conv_fwd(const void* X, const void* W, void* Y, const lrd_conv_geom* g,
@@ -858,7 +865,14 @@ lrd_status lrd_dense_conv_bwd(const void* dY, const void* X, const void* W, void
         wg = tn(dY, g->S, X, g->C, dW, kk * g->C, g->S, kk * g->C, pout, dt);
         wg.gather = GATHER_CONV_WGRAD;
         wg.cs = cs;
-        attach_splits(wg, cv, dt);
+        // the workgroup partials of the direct kernel, or split-K slices, in the same region
+        const size_t direct = conv_direct_wgrad_bytes(cs, dt == LRD_BF16);
+        if (direct) {
+            wg.scratch = cv.take(direct);
+            wg.scratch_bytes = direct;
+        } else {
+            attach_splits(wg, cv, dt);
+        }
         if (!cv.ok) return LRD_ERR_WORKSPACE;
     }
     if (dX) {

@@ -42,6 +42,10 @@ struct MatOp {
     int epilogue = 0;
     void* aux = nullptr;
     int64_t ldaux = 0;
+    // Optional device scratch an engine may use (the direct convolution's weight gradient keeps
+    // its per-workgroup partial sums there).
+    void* scratch = nullptr;
+    size_t scratch_bytes = 0;
 };
 enum { EPI_NONE = 0, EPI_ACT_STORE = 1, EPI_ACT_GRAD = 2 };
 
@@ -51,6 +55,9 @@ bool mfma_matop_supported(const MatOp& op);                         // bf16 MFMA
 hipError_t mfma_matop(const MatOp& op, hipStream_t st);
 bool mfma_gemm2_supported(const MatOp& op);                        // aligned fast path covers it?
 hipError_t mfma_gemm2(const MatOp& op, hipStream_t st);
+bool conv_direct_supported(const MatOp& op);                       // 3 x 3 stride-1 convolution with 32 / 64 channels?
+hipError_t conv_direct(const MatOp& op, hipStream_t st);
+size_t conv_direct_wgrad_bytes(const ConvShape& cs, bool bf16);    // scratch its weight gradient wants (0: not covered)
 hipError_t run_matop(const MatOp& op, hipStream_t st);              // picks an engine
 hipError_t apply_epilogue(const MatOp& op, hipStream_t st);        // unfused form of MatOp::epilogue
 

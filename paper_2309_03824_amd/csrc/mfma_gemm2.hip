@@ -392,25 +392,7 @@ __device__ __forceinline__ bf16x8 kc_frag(const bf16_t* tile, int row_block, int
     return *reinterpret_cast<const bf16x8*>(tile + (row_block * 32 + (lane & 31)) * LDK + kk * 16 + (lane >> 5) * 8);
 }
 
-// k-major tile [k][row]: two transposing reads.  Within a block of 16 lanes, ds_read_b64_tr_b16
-// hands lane l the element (l & 3) of the 8-byte words addressed by lanes (l >> 2) + 4e, e = 0..3.
-// Pointing lane s at [k = kb + (s >> 2)][row = rb + 4 * (s & 3)] therefore gives lane l the four
-// values k = kb..kb+3 of row rb + l.
-template <int LDM>
-__device__ __forceinline__ bf16x8 km_frag(const bf16_t* tile, int row_block, int kk, int lane)
-{
-    typedef short s16x4 __attribute__((ext_vector_type(4)));
-    typedef short s16x8 __attribute__((ext_vector_type(8)));
-    const int blk = lane >> 4, s = lane & 15;
-    const int rb = row_block * 32 + 16 * (blk & 1) + 4 * (s & 3);
-    const int kb = kk * 16 + 8 * (blk >> 1) + (s >> 2);
-    const bf16_t* p = tile + kb * LDM + rb;
-    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p + 4 * LDM));
-    s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-    return __builtin_bit_cast(bf16x8, v);
-}
-
+// k-major tile [k][row]: km_frag (two transposing reads).
 template <int TM, int TN, bool A_KM, bool B_KM, int LDMA, int LDMB>
 __device__ __forceinline__ void mma_step(f32x16 (&acc)[TM][TN], const bf16_t* a_lds, int a_row0, const bf16_t* b_lds,
                                          int b_row0, int lane)

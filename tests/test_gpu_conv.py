@@ -101,6 +101,20 @@ def test_strided_stage_transitions_bf16():
         run_tucker(2, hw, hw, C, 2 * C, C // 2, C, 3, 2, 1, "bf16", 0, seed=71 + C)
 
 
+@pytest.mark.parametrize("geo", [
+    (2, 13, 37, 48, 40, 32, 32, 3, 1, 1),    # ragged in both directions, two column tiles
+    (1, 9, 33, 40, 72, 32, 64, 3, 1, 0),     # no padding, unequal ranks, one pixel past a column tile
+    (2, 17, 31, 64, 64, 64, 32, 3, 1, 2),    # padding 2 (output larger than input)
+    (1, 8, 32, 64, 64, 64, 64, 3, 1, 1),     # exactly one tile
+    (3, 5, 70, 32, 32, 30, 30, 3, 1, 1),     # ranks padded to 32, three column tiles
+])
+def test_small_rank_core_geometries_bf16(geo):
+    """3 x 3 stride-1 cores with ranks 32 / 64 (the early ResNet stages) take the patch-staging
+    convolution kernel in forward and data gradient: tile edges, paddings 0..2, rank mixes."""
+    run_tucker(*geo, "bf16", 0, seed=sum(geo))
+    run_tucker(*geo, "bf16", lrd.freeze_mask(lrd.KIND_TUCKER, 1), seed=sum(geo) + 1, save=False)
+
+
 def test_tucker_rank_cliff_shapes_bf16():
     """Ranks one off a tile boundary (the 257 -> 256 situation of Section 2.1) must stay correct."""
     for r in (31, 33, 65, 127):
@@ -110,7 +124,8 @@ def test_tucker_rank_cliff_shapes_bf16():
 @pytest.mark.parametrize("dt", ["bf16", "f32"])
 def test_dense_conv(dt):
     for (N, Hh, Ww, C, S, k, stride, pad) in ((2, 9, 7, 24, 40, 3, 1, 1), (1, 12, 12, 16, 8, 3, 2, 1),
-                                              (2, 14, 14, 64, 64, 3, 1, 1), (1, 6, 6, 5, 3, 5, 1, 2)):
+                                              (2, 14, 14, 64, 64, 3, 1, 1), (1, 6, 6, 5, 3, 5, 1, 2),
+                                              (2, 11, 35, 32, 64, 3, 1, 1)):
         rng = np.random.Generator(np.random.PCG64(N * 1000 + C))
         X, W = si.gaussian((N, Hh, Ww, C), rng), si.conv_weight(S, C, k, rng)
         g = lrd.conv_geom(N, Hh, Ww, C, S, 1, 1, k, stride, pad)
@@ -127,3 +142,32 @@ def test_dense_conv(dt):
         check(host(Y_), oracle.conv_fwd(Xo, Wo_, stride, pad), dt, "Y")
         check(host(gX), oracle.conv_dgrad(dYo, Wo_, (Hh, Ww), stride, pad), dt, "dX")
         check(host(gW), oracle.conv_wgrad(dYo, Xo, k, stride, pad), dt, "dW")
+
+
+@pytest.mark.parametrize("C,hw", [(32, 56), (64, 28)])
+def test_core_layer_full_size_sampled_bf16(C, hw):
+    """The 3 x 3 core of the first two ResNet stages at full size (128 images, ranks 32 at 56 x 56 and
+    64 at 28 x 28), where every workgroup of the patch-staging kernels walks over several tiles.  The
+    oracle evaluates sampled images: their outputs and input gradients, and the weight gradient of an
+    output gradient that is zero on all other images."""
+    N, k = 128, 3
+    picks = [0, 1, 17, 42, 63, 64, 100, 127]
+    rng = si.rng_for(4, 900 + C)
+    X = si.gaussian((N, hw, hw, C), rng).astype(np.float32)
+    W = si.conv_weight(C, C, k, rng)
+    dY = np.zeros((N, hw, hw, C), dtype=np.float32)
+    dY[picks] = si.gaussian((len(picks), hw, hw, C), rng)
+    g = lrd.conv_geom(N, hw, hw, C, C, 1, 1, k, 1, 1)
+    X_, W_, dY_ = dev(X, "bf16"), dev(W, "bf16"), dev(dY, "bf16")
+    Y_ = empty((N, hw, hw, C), "bf16")
+    ws = workspace(lrd.dense_conv_workspace_bytes(g, code("bf16")))
+    lrd.dense_conv_fwd(X_, W_, Y_, g, ws)
+    gX, gW = empty((N, hw, hw, C), "bf16"), f32((C, k, k, C))
+    lrd.dense_conv_bwd(dY_, X_, W_, gX, gW, g, ws)
+    torch.cuda.synchronize()
+    Xo, Wo_, dYo = seen(X[picks], "bf16"), seen(W, "bf16"), seen(dY[picks], "bf16")
+    check(host(Y_[picks]), oracle.conv_fwd(Xo, Wo_, 1, 1), "bf16", "Y")
+    check(host(gX[picks]), oracle.conv_dgrad(dYo, Wo_, (hw, hw), 1, 1), "bf16", "dX")
+    check(host(gW), oracle.conv_wgrad(dYo, Xo, k, 1, 1), "bf16", "dW")
+    rest = [n for n in range(N) if n not in picks]
+    assert torch.all(gX[rest] == 0), "input gradient of an image whose output gradient is zero"
