@@ -281,6 +281,41 @@ def rank_sweep(args, torch, lrd):
                           points=points)))
 
 
+def conv_stage(args, torch, lrd):
+    """One 3x3 stage of config 4 (N = 128, Tucker ranks C/2) and the dense layer beside it: forward and
+    the backward with nothing frozen, a few times, for a kernel trace.  Prints one JSON line."""
+    bf = torch.bfloat16
+    gen = torch.Generator(device="cuda").manual_seed(230903824 + 4)
+    C = args.conv_stage
+    hw = {64: 56, 128: 28, 256: 14, 512: 7}[C]
+    N, k, r = 128, 3, C // 2
+
+    def rnd(*shape, scale=1.0):
+        return (torch.randn(*shape, device="cuda", generator=gen) * scale).to(bf)
+
+    def empty(*shape, dt=bf):
+        return torch.empty(*shape, dtype=dt, device="cuda")
+
+    g = lrd.conv_geom(N, hw, hw, C, C, r, r, k, 1, 1)
+    X, dY, Y, dX = rnd(N, hw, hw, C), rnd(N, hw, hw, C), empty(N, hw, hw, C), empty(N, hw, hw, C)
+    P1, G, P2 = rnd(r, C, scale=C ** -0.5), rnd(r, k, k, r, scale=(k * k * r) ** -0.5), rnd(C, r, scale=r ** -0.5)
+    A, B = empty(N, hw, hw, r), empty(N, hw, hw, r)
+    dP1, dG, dP2 = empty(r, C, dt=torch.float32), empty(r, k, k, r, dt=torch.float32), empty(C, r, dt=torch.float32)
+    W, dW = rnd(C, k, k, C, scale=(k * k * C) ** -0.5), empty(C, k, k, C, dt=torch.float32)
+    ws = torch.empty(lrd.tucker_conv_workspace_bytes(g, lrd.BF16, 0) + 256, dtype=torch.uint8, device="cuda")
+    wsd = torch.empty(lrd.dense_conv_workspace_bytes(g, lrd.BF16) + 256, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    iters = 5
+    for _ in range(iters):
+        lrd.tucker_conv_fwd(X, P1, G, P2, Y, A, B, g, ws)
+        lrd.tucker_conv_bwd(dY, X, A, B, P1, G, P2, dX, dP1, dG, dP2, 0, g, ws)
+    for _ in range(iters):
+        lrd.dense_conv_fwd(X, W, Y, g, wsd)
+        lrd.dense_conv_bwd(dY, X, W, dX, dW, g, wsd)
+    torch.cuda.synchronize()
+    print(json.dumps(dict(metric="conv stage kernel trace run", C=C, hw=hw, N=N, r=r, iters=iters)), flush=True)
+
+
 def layer_tables(args, torch, lrd):
     """Configs 4 and 5, layer by layer: the four ResNet-style 3x3 stages (N = 128, Tucker ranks C/2 and
     the raw ranks next to them, core frozen / 1x1s frozen / nothing frozen, beside the dense conv) and
@@ -583,6 +618,8 @@ def main():
     ap.add_argument("--factorize", action="store_true", help="time the on-device factorization (SVD pairs, Tucker-2) instead")
     ap.add_argument("--layer-tables", action="store_true",
                     help="time the Tucker conv stages (config 4) and the transformer projections (config 5) instead")
+    ap.add_argument("--conv-stage", type=int, default=0, choices=(0, 64, 128, 256, 512),
+                    help="run one 3x3 stage of config 4 (Tucker and dense, forward + backward) a few times, for a kernel trace")
     ap.add_argument("--sweep-step", type=int, default=16)
     ap.add_argument("--sweep-iters", type=int, default=5)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -606,6 +643,9 @@ def main():
 
     if args.rank_sweep:
         rank_sweep(args, torch, lrd)
+        return
+    if args.conv_stage:
+        conv_stage(args, torch, lrd)
         return
     if args.layer_tables:
         layer_tables(args, torch, lrd)
