@@ -179,8 +179,10 @@ lrd_status lrd_sgd_step(float* w_master, float* momentum_buf, const float* grad,
 
 /*
  * lrd_linear_bwd_act followed by that step for every factor freeze_mask leaves trainable, in one
- * call: the weight gradients stay in the workspace, a frozen factor costs neither a gradient nor an
- * update (Section 2.2 carried through the optimizer).  V and U are the compute copies the layer
+ * call: a frozen factor costs neither a gradient nor an update (Section 2.2 carried through the
+ * optimizer), and a trainable factor's step is applied where its gradient is finished: inside the
+ * fixed-order sum over the K-slices of the weight-gradient product when that product is sliced (the
+ * gradient is then never stored), else on the gradient in the workspace right after the product.  V and U are the compute copies the layer
  * multiplies with (dtype dt) and are rewritten; V_master / U_master and V_momentum / U_momentum are
  * fp32 [r x in] / [out x r], required for the trainable factors, ignored for frozen ones.  The data
  * gradient dX uses the factors as they were before the update.  Other arguments as lrd_linear_bwd_act;

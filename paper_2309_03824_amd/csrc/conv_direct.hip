@@ -488,7 +488,7 @@ hipError_t conv_direct(const MatOp& op, hipStream_t st)
     default: e = launch_wgrad<64, 64>(B, A, partial, cs.N, cs.H, cs.W, cs.Ho, cs.Wo, cs.pad, &slices, st); break;
     }
     if (e != hipSuccess) return e;
-    return reduce_partials(partial, op.C, false, op.ldc, cs.O, 9 * (int64_t)cs.I, slices, st);
+    return reduce_partials(partial, op.C, false, op.ldc, cs.O, 9 * (int64_t)cs.I, slices, st, op.sgd);
 }
 
 }  // namespace lrd

@@ -94,6 +94,13 @@ hipError_t run_matop(const MatOp& op_in, hipStream_t st)
         if (mfma_matop_supported(op)) e = mfma_matop(op, st);
         else e = generic_matop(op, st);
     }
+    if (e == hipSuccess && op.sgd && !op.sgd->done) {
+        // the engine stored the gradient whole: the step runs on it as a kernel of its own
+        if (!op.out_f32 || op.ldc != op.N) e = hipErrorInvalidValue;
+        else e = sgd_step(op.sgd->w, op.sgd->m, (const float*)op.C, op.sgd->copy, op.sgd->copy_bf16, op.M * op.N, op.sgd->lr,
+                          op.sgd->mu, op.sgd->wd, st);
+        op.sgd->done = true;
+    }
     if (probed) (void)hipEventRecord(ev1, st);
     if (e != hipSuccess || epilogue_done) return e;
     return apply_epilogue(op, st);

@@ -72,12 +72,36 @@ __global__ __launch_bounds__(256) void column_sums_kernel(const T* __restrict__ 
     if (lane == 0 && col < n) out[col] = (part[0][c] + part[1][c]) + (part[2][c] + part[3][c]);
 }
 
+// The optimizer step of sgd_step_kernel on four consecutive weights whose gradient g has just been
+// summed (same arithmetic, so that a step does not depend on where it ran).
+struct SgdArgs { float* w; float* m; void* copy; int copy_bf16; float lr, mu, wd; };
+__device__ __forceinline__ void sgd_apply4(const SgdArgs& a, int64_t i, f32x4 g)
+{
+    f32x4 w = *reinterpret_cast<const f32x4*>(a.w + i), m = *reinterpret_cast<const f32x4*>(a.m + i);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        m[e] = fmaf(a.mu, m[e], fmaf(a.wd, w[e], g[e]));
+        w[e] = fmaf(-a.lr, m[e], w[e]);
+    }
+    *reinterpret_cast<f32x4*>(a.m + i) = m;
+    *reinterpret_cast<f32x4*>(a.w + i) = w;
+    if (a.copy) {
+        if (a.copy_bf16) {
+            u32x2 pk = {pack_bf16(w[0], w[1]), pack_bf16(w[2], w[3])};
+            *reinterpret_cast<u32x2*>(reinterpret_cast<bf16_t*>(a.copy) + i) = pk;
+        } else {
+            *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.copy) + i) = w;
+        }
+    }
+}
+
 // C[m][n] = sum_z partial[z][m][n], slices added in ascending z so the result does not depend on
 // scheduling.  VEC consecutive columns per thread (N and ldc are multiples of VEC); OutT is the
 // result type (fp32 weight gradients, or bf16 activations rounded once from the fp32 sum).
-template <int VEC, class OutT>
+// With SGD (VEC == 4, fp32, ldc == N) the sum feeds the optimizer step and is not stored.
+template <int VEC, class OutT, bool SGD = false>
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, OutT* __restrict__ C,
-                                                              int64_t ldc, int64_t M, int64_t N, int splits)
+                                                              int64_t ldc, int64_t M, int64_t N, int splits, SgdArgs sgd = SgdArgs{})
 {
     const int64_t total = M * N;
     const int64_t groups = total / VEC;
@@ -106,7 +130,8 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
             *reinterpret_cast<u32x4*>(out) = pk;
         } else if constexpr (VEC == 4 && sizeof(OutT) == 4) {
             f32x4 v = {s[0], s[1], s[2], s[3]};
-            *reinterpret_cast<f32x4*>(out) = v;
+            if constexpr (SGD) sgd_apply4(sgd, i, v);
+            else *reinterpret_cast<f32x4*>(out) = v;
         } else {
 #pragma unroll
             for (int e = 0; e < VEC; ++e) out[e] = from_f32<OutT>(s[e]);
@@ -119,9 +144,10 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
 // the slices one after the other, so LANES threads share a group of 4 outputs, thread l adds slices
 // l, l + LANES, ... in ascending order and the LANES sums are combined in ascending l.  Still a
 // fixed order.
-template <int LANES>
+template <int LANES, bool SGD = false>
 __global__ __launch_bounds__(256) void reduce_partials_wide_kernel(const float* __restrict__ partial, float* __restrict__ C,
-                                                                   int64_t ldc, int64_t M, int64_t N, int splits)
+                                                                   int64_t ldc, int64_t M, int64_t N, int splits,
+                                                                   SgdArgs sgd = SgdArgs{})
 {
     constexpr int GROUPS = 256 / LANES;       // groups of 4 outputs per block
     __shared__ f32x4 part[LANES][GROUPS + 1];
@@ -138,7 +164,8 @@ __global__ __launch_bounds__(256) void reduce_partials_wide_kernel(const float* 
 #pragma unroll
         for (int q = 1; q < LANES; ++q) t += part[q][gl];
         const int64_t i = g * 4;
-        *reinterpret_cast<f32x4*>(C + (i / N) * ldc + (i % N)) = t;
+        if constexpr (SGD) sgd_apply4(sgd, i, t);
+        else *reinterpret_cast<f32x4*>(C + (i / N) * ldc + (i % N)) = t;
     }
 }
 
@@ -234,31 +261,49 @@ hipError_t sgd_step(float* w, float* m, const float* g, void* copy, bool copy_bf
 }
 
 hipError_t reduce_partials(const float* partial, void* C, bool c_bf16, int64_t ldc, int64_t M, int64_t N, int splits,
-                           hipStream_t st)
+                           hipStream_t st, const SgdFuse* sgd)
 {
     if (M <= 0 || N <= 0) return hipSuccess;
-    const bool al = (reinterpret_cast<uintptr_t>(C) & 15u) == 0 && (reinterpret_cast<uintptr_t>(partial) & 15u) == 0;
+    auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
+    const bool al = al16(C) && al16(partial);
     if (c_bf16) {
         if (al && N % 8 == 0 && ldc % 8 == 0)
             hipLaunchKernelGGL((reduce_partials_kernel<8, bf16_t>), dim3(blocks_for(M * N / 8)), dim3(256), 0, st, partial,
-                               (bf16_t*)C, ldc, M, N, splits);
+                               (bf16_t*)C, ldc, M, N, splits, SgdArgs{});
         else
             hipLaunchKernelGGL((reduce_partials_kernel<1, bf16_t>), dim3(blocks_for(M * N)), dim3(256), 0, st, partial,
-                               (bf16_t*)C, ldc, M, N, splits);
-    } else {
-        if (al && N % 4 == 0 && ldc % 4 == 0 && splits >= 64 && M * N / 4 <= 4096)
-            hipLaunchKernelGGL(reduce_partials_wide_kernel<64>, dim3((unsigned)ceil_div(M * N / 4, 4)), dim3(256), 0, st, partial,
-                               (float*)C, ldc, M, N, splits);
-        else if (al && N % 4 == 0 && ldc % 4 == 0 && splits >= 16 && M * N / 4 < 256 * 256)
-            hipLaunchKernelGGL(reduce_partials_wide_kernel<16>, dim3((unsigned)ceil_div(M * N / 4, 16)), dim3(256), 0, st, partial,
-                               (float*)C, ldc, M, N, splits);
-        else if (al && N % 4 == 0 && ldc % 4 == 0)
-            hipLaunchKernelGGL((reduce_partials_kernel<4, float>), dim3(blocks_for(M * N / 4)), dim3(256), 0, st, partial,
-                               (float*)C, ldc, M, N, splits);
-        else
-            hipLaunchKernelGGL((reduce_partials_kernel<1, float>), dim3(blocks_for(M * N)), dim3(256), 0, st, partial,
-                               (float*)C, ldc, M, N, splits);
+                               (bf16_t*)C, ldc, M, N, splits, SgdArgs{});
+        return hipGetLastError();
     }
+    const bool vec4 = al && N % 4 == 0 && ldc % 4 == 0;
+    const bool wide64 = vec4 && splits >= 64 && M * N / 4 <= 4096;
+    const bool wide16 = vec4 && splits >= 16 && M * N / 4 < 256 * 256;
+    if (sgd && !sgd->done && vec4 && ldc == N && al16(sgd->w) && al16(sgd->m) && (reinterpret_cast<uintptr_t>(sgd->copy) & 15u) == 0) {
+        const SgdArgs a{sgd->w, sgd->m, sgd->copy, sgd->copy_bf16 ? 1 : 0, sgd->lr, sgd->mu, sgd->wd};
+        if (wide64)
+            hipLaunchKernelGGL((reduce_partials_wide_kernel<64, true>), dim3((unsigned)ceil_div(M * N / 4, 4)), dim3(256), 0, st,
+                               partial, (float*)C, ldc, M, N, splits, a);
+        else if (wide16)
+            hipLaunchKernelGGL((reduce_partials_wide_kernel<16, true>), dim3((unsigned)ceil_div(M * N / 4, 16)), dim3(256), 0, st,
+                               partial, (float*)C, ldc, M, N, splits, a);
+        else
+            hipLaunchKernelGGL((reduce_partials_kernel<4, float, true>), dim3(blocks_for(M * N / 4)), dim3(256), 0, st, partial,
+                               (float*)C, ldc, M, N, splits, a);
+        sgd->done = true;
+        return hipGetLastError();
+    }
+    if (wide64)
+        hipLaunchKernelGGL((reduce_partials_wide_kernel<64>), dim3((unsigned)ceil_div(M * N / 4, 4)), dim3(256), 0, st, partial,
+                           (float*)C, ldc, M, N, splits, SgdArgs{});
+    else if (wide16)
+        hipLaunchKernelGGL((reduce_partials_wide_kernel<16>), dim3((unsigned)ceil_div(M * N / 4, 16)), dim3(256), 0, st, partial,
+                           (float*)C, ldc, M, N, splits, SgdArgs{});
+    else if (vec4)
+        hipLaunchKernelGGL((reduce_partials_kernel<4, float>), dim3(blocks_for(M * N / 4)), dim3(256), 0, st, partial,
+                           (float*)C, ldc, M, N, splits, SgdArgs{});
+    else
+        hipLaunchKernelGGL((reduce_partials_kernel<1, float>), dim3(blocks_for(M * N)), dim3(256), 0, st, partial,
+                           (float*)C, ldc, M, N, splits, SgdArgs{});
     return hipGetLastError();
 }
 

@@ -164,7 +164,7 @@ hipError_t launch(const MatOp& op, hipStream_t st)
                        op.ldc, op.bias, partial, kps);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (splits > 1) return reduce_partials(op.partial, op.C, false, op.ldc, op.M, op.N, splits, st);
+    if (splits > 1) return reduce_partials(op.partial, op.C, false, op.ldc, op.M, op.N, splits, st, op.sgd);
     return hipSuccess;
 }
 

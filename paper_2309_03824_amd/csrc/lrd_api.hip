@@ -296,10 +296,13 @@ lrd_status lrd_linear_bwd(const void* dY, const void* X, const void* H, const vo
                               dt, ws, ws_bytes, hip_stream);
 }
 
-lrd_status lrd_linear_bwd_act(const void* dY, const void* X, const void* H, const void* V,
-                              const void* U, void* dX, float* dV, float* dU, float* dbias,
-                              uint32_t freeze_mask, const void* Z_in, int32_t act, int64_t T, int64_t in,
-                              int64_t out, int64_t r, lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream)
+namespace {
+// lrd_linear_bwd_act; with sgd_u / sgd_v the optimizer step of that factor is applied where its
+// gradient is finished (no padded ranks then: their gradients are cropped first).
+lrd_status linear_bwd_impl(const void* dY, const void* X, const void* H, const void* V, const void* U, void* dX, float* dV,
+                           float* dU, float* dbias, uint32_t freeze_mask, const void* Z_in, int32_t act, int64_t T,
+                           int64_t in, int64_t out, int64_t r, lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream,
+                           const SgdFuse* sgd_u, const SgdFuse* sgd_v)
 {
     if (!dtype_ok(dt) || !linear_dims_ok(T, in, out, r) || !dY || !V || !U) return LRD_ERR_INVALID_ARG;
     if ((act != LRD_ACT_NONE && act != LRD_ACT_GELU) || (act == LRD_ACT_GELU && dX && !Z_in)) return LRD_ERR_INVALID_ARG;
@@ -326,6 +329,7 @@ lrd_status lrd_linear_bwd_act(const void* dY, const void* X, const void* H, cons
         LRD_TRY(copy2d(V, in, r, in, Vp, in, r8, in, 2, st));
         const bool have_h = H && train_u;
         if (have_h) LRD_TRY(copy2d(H, r, T, r, Hp, r8, T, r8, 2, st));
+        if (sgd_u || sgd_v) return LRD_ERR_INVALID_ARG;
         lrd_status rc = lrd_linear_bwd_act(dY, X, have_h ? Hp : nullptr, Vp, Up, dX, dVp, dUp, dbias, freeze_mask, Z_in, act, T,
                                            in, out, r8, dt, (char*)ws + cvp.used, ws_bytes - cvp.used, hip_stream);
         if (rc != LRD_OK) return rc;
@@ -346,11 +350,13 @@ lrd_status lrd_linear_bwd_act(const void* dY, const void* X, const void* H, cons
     if (train_u) {
         wu = tn(dY, out, H ? H : Hre, r, dU, r, out, r, T, dt);
         wu.role = LRD_ROLE_WGRAD_U;
+        wu.sgd = sgd_u;
         share_splits(wu, region, dt, SPLIT_WGRAD);
     }
     if (train_v) {
         wv = tn(dH, r, X, in, dV, in, r, in, T, dt);
         wv.role = LRD_ROLE_WGRAD_V;
+        wv.sgd = sgd_v;
         share_splits(wv, region, dt, SPLIT_WGRAD);
     }
     if (!cv.ok) return LRD_ERR_WORKSPACE;
@@ -401,6 +407,16 @@ lrd_status lrd_linear_bwd_act(const void* dY, const void* X, const void* H, cons
     if (dbias) LRD_TRY(column_sums(dY, dbias, T, out, dt == LRD_BF16, st));
     return LRD_OK;
 }
+}  // namespace
+
+lrd_status lrd_linear_bwd_act(const void* dY, const void* X, const void* H, const void* V,
+                              const void* U, void* dX, float* dV, float* dU, float* dbias,
+                              uint32_t freeze_mask, const void* Z_in, int32_t act, int64_t T, int64_t in,
+                              int64_t out, int64_t r, lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    return linear_bwd_impl(dY, X, H, V, U, dX, dV, dU, dbias, freeze_mask, Z_in, act, T, in, out, r, dt, ws, ws_bytes, hip_stream,
+                           nullptr, nullptr);
+}
 
 // ------------------------------------------------------------------------------------ optimizer
 lrd_status lrd_sgd_step(float* w_master, float* momentum_buf, const float* grad, void* w_copy, lrd_dtype copy_dt, int64_t n,
@@ -437,14 +453,26 @@ lrd_status lrd_linear_bwd_sgd(const void* dY, const void* X, const void* H, void
     float* dU = train_u ? (float*)cv.take((size_t)out * r * 4) : nullptr;
     float* dV = train_v ? (float*)cv.take((size_t)r * in * 4) : nullptr;
     if (!cv.ok) return LRD_ERR_WORKSPACE;
-    lrd_status rc = lrd_linear_bwd_act(dY, X, H, V, U, dX, dV, dU, dbias, freeze_mask, Z_in, act, T, in, out, r, dt,
-                                       (char*)ws + cv.used, ws_bytes - cv.used, hip_stream);
-    if (rc != LRD_OK) return rc;
-    hipStream_t st = (hipStream_t)hip_stream;
-    // the data gradients above read V and U; the stream orders the updates after them
-    if (train_u) LRD_TRY(sgd_step(U_master, U_momentum, dU, U, dt == LRD_BF16, out * r, opt->lr, opt->momentum, opt->weight_decay, st));
-    if (train_v) LRD_TRY(sgd_step(V_master, V_momentum, dV, V, dt == LRD_BF16, r * in, opt->lr, opt->momentum, opt->weight_decay, st));
-    return LRD_OK;
+    if (pads_rank(in, out, r, dt)) {
+        // padded ranks: the gradients are cropped to the caller's rank before the steps
+        lrd_status rc = lrd_linear_bwd_act(dY, X, H, V, U, dX, dV, dU, dbias, freeze_mask, Z_in, act, T, in, out, r, dt,
+                                           (char*)ws + cv.used, ws_bytes - cv.used, hip_stream);
+        if (rc != LRD_OK) return rc;
+        hipStream_t st = (hipStream_t)hip_stream;
+        if (train_u) LRD_TRY(sgd_step(U_master, U_momentum, dU, U, true, out * r, opt->lr, opt->momentum, opt->weight_decay, st));
+        if (train_v) LRD_TRY(sgd_step(V_master, V_momentum, dV, V, true, r * in, opt->lr, opt->momentum, opt->weight_decay, st));
+        return LRD_OK;
+    }
+    // Each step is applied where its gradient is finished: in the sum over the split-K slices (the
+    // gradient itself is then never stored), else by a kernel right after the product.  Both weight
+    // gradients come after every product that reads V or U, and dV does not read U.
+    SgdFuse su, sv;
+    su.w = U_master; su.m = U_momentum; su.copy = U;
+    sv.w = V_master; sv.m = V_momentum; sv.copy = V;
+    su.copy_bf16 = sv.copy_bf16 = dt == LRD_BF16;
+    su.lr = sv.lr = opt->lr; su.mu = sv.mu = opt->momentum; su.wd = sv.wd = opt->weight_decay;
+    return linear_bwd_impl(dY, X, H, V, U, dX, dV, dU, dbias, freeze_mask, Z_in, act, T, in, out, r, dt, (char*)ws + cv.used,
+                           ws_bytes - cv.used, hip_stream, train_u ? &su : nullptr, train_v ? &sv : nullptr);
 }
 
 // ------------------------------------------------------------------------------------ grouped linear

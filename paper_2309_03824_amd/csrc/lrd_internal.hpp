@@ -15,6 +15,18 @@ enum Gather : int {
     GATHER_CONV_WGRAD = 3   // B rows are taps (u,v,i), K runs over output pixels
 };
 
+// An SGD step (see sgd_step) to be applied to a weight where its gradient is finished.  An engine
+// that sums split-K partials applies it in that sum and never stores the gradient; otherwise
+// run_matop runs it as a kernel of its own on the stored gradient.  Either way `done` is set.
+struct SgdFuse {
+    float* w = nullptr;        // fp32 master weights, same shape as the gradient (dense)
+    float* m = nullptr;        // momentum buffer
+    void* copy = nullptr;      // compute copy of the weights to refresh (optional)
+    bool copy_bf16 = false;
+    float lr = 0.f, mu = 0.f, wd = 0.f;
+    mutable bool done = false;
+};
+
 // One product  C[M x N] = A[M x K] . B[N x K]^T (+ bias[n]),  fp32 accumulation.
 // A(m,k) = A[m*a_sm + k*a_sk], B(n,k) = B[n*b_sn + k*b_sk] (element strides) unless a gather mode
 // replaces the addressing of one operand by a convolution's tap geometry.
@@ -46,6 +58,8 @@ struct MatOp {
     // its per-workgroup partial sums there).
     void* scratch = nullptr;
     size_t scratch_bytes = 0;
+    // Optional optimizer step on the finished fp32 result (a dense weight gradient, ldc == N).
+    const SgdFuse* sgd = nullptr;
 };
 enum { EPI_NONE = 0, EPI_ACT_STORE = 1, EPI_ACT_GRAD = 2 };
 
@@ -95,7 +109,9 @@ hipError_t copy2d(const void* src, int64_t ld_src, int64_t rows_src, int64_t col
 hipError_t sgd_step(float* w, float* m, const float* g, void* copy, bool copy_bf16, int64_t n, float lr, float mu, float wd,
                     hipStream_t st);
 // C = sum over split-K slices of partial[z][M][N], ascending z; C is fp32 or (c_bf16) bf16.
+// With `sgd` (fp32 results only) the sum is used for that step instead of being stored, when the
+// layout allows (then sgd->done is set).
 hipError_t reduce_partials(const float* partial, void* C, bool c_bf16, int64_t ldc, int64_t M, int64_t N,
-                           int splits, hipStream_t st);
+                           int splits, hipStream_t st, const SgdFuse* sgd = nullptr);
 
 }  // namespace lrd

@@ -473,7 +473,7 @@ hipError_t launch_gemm(const MatOp& op, const Src& A, const Src& B, hipStream_t 
                        (int)op.M, (int)op.N, kps, cvec);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (splits > 1) return reduce_partials(op.partial, op.C, false, op.ldc, op.M, op.N, splits, st);
+    if (splits > 1) return reduce_partials(op.partial, op.C, false, op.ldc, op.M, op.N, splits, st, op.sgd);
     return hipSuccess;
 }
 

@@ -647,7 +647,7 @@ hipError_t launch(const MatOp& op, const Operand& A, const Operand& B, hipStream
                        (int)op.N, (int)op.K, kps, op.epilogue, (bf16_t*)op.aux, op.ldaux);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (splits > 1) return reduce_partials(op.partial, op.C, !op.out_f32, op.ldc, op.M, op.N, splits, st);
+    if (splits > 1) return reduce_partials(op.partial, op.C, !op.out_f32, op.ldc, op.M, op.N, splits, st, op.out_f32 ? op.sgd : nullptr);
     return hipSuccess;
 }
 

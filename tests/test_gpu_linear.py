@@ -298,9 +298,16 @@ def test_grouped_linear_matches_separate_oracle_layers(dt, case):
 
 # ---------------------------------------------------------------- backward + optimizer step in one call
 @pytest.mark.parametrize("dt", ["bf16", "f32"])
-def test_backward_with_sgd_update(dt):
-    T, n_in, n_out, r = 384, 96, 160, 32
-    rng = si.rng_for(5, 900)
+@pytest.mark.parametrize("shape", [
+    (384, 96, 160, 32),      # gradients stored whole: the step is a kernel of its own
+    (1024, 192, 256, 64),    # 4 K-slices: the step runs in the sum over the slices
+    (4096, 192, 256, 64),    # 16 slices, several threads per output in the sum
+    (16384, 64, 64, 64),     # 64 slices
+    (384, 96, 160, 30),      # rank padded to 32 inside: gradients cropped before the step
+])
+def test_backward_with_sgd_update(dt, shape):
+    T, n_in, n_out, r = shape
+    rng = si.rng_for(5, 900 + T + r)
     X, dY = si.gaussian((T, n_in), rng), si.gaussian((T, n_out), rng)
     U0, V0 = si.direct_factors(n_out, n_in, r, rng)
     opt = lrd.Sgd(0.05, 0.9, 1e-4)
