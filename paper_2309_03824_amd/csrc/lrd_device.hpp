@@ -92,6 +92,21 @@ struct ConvShape {
     int Ho, Wo;      // output height / width
     int I, O;        // input / output channels of THIS convolution
     int k, stride, pad;
+    // Data gradient of a strided convolution, one parity class at a time: with cls set, the rows of
+    // the product are the input pixels with y = cy, x = cx (mod stride) only, and its K runs over
+    // the taps that can reach such a pixel (class_taps), not over all k * k.
+    int cls = 0, cy = 0, cx = 0;
 };
+
+// Taps u = first + stride * t, t = 0 .. count - 1, through which an input coordinate congruent to c
+// (mod stride) receives from an output coordinate: u = c + pad - stride * (output coordinate).
+struct ClassTaps { int first, count; };
+__host__ __device__ __forceinline__ ClassTaps class_taps(int c, int pad, int stride, int k)
+{
+    const int f = (c + pad) % stride;
+    return {f, f < k ? (k - 1 - f) / stride + 1 : 0};
+}
+// Input coordinates congruent to c (mod stride) below extent.
+__host__ __device__ __forceinline__ int class_extent(int extent, int c, int stride) { return extent > c ? (extent - c + stride - 1) / stride : 0; }
 
 }  // namespace lrd

@@ -190,6 +190,7 @@ struct ConvRowsTile {
     bool rowok[CH];
     int kc8, tap, c0;         // this thread's k of the next load, as (tap, channel); same for all its chunks
     int ch, q_tap, r_ch, magic, magic_s;
+    int kdiv, u0, v0, ustep;  // tap index -> (u, v): u = u0 + ustep * (tap / kdiv), v = v0 + ustep * (tap % kdiv)
     bool ok[DEPTH][CH];
     u32x4 st[DEPTH][CH];
 
@@ -200,12 +201,20 @@ struct ConvRowsTile {
         ch = DGRAD ? cs.O : cs.I;            // channels of the tensor being gathered
         q_tap = BK / ch;
         r_ch = BK - q_tap * ch;
-        magic = (65536 + cs.k - 1) / cs.k;
+        const bool cls = DGRAD && cs.cls;
+        const ClassTaps tu = class_taps(cs.cy, cs.pad, cs.stride, cs.k), tv = class_taps(cs.cx, cs.pad, cs.stride, cs.k);
+        kdiv = cls ? tv.count : cs.k;
+        u0 = cls ? tu.first : 0;
+        v0 = cls ? tv.first : 0;
+        ustep = cls ? cs.stride : 1;
+        magic = (65536 + kdiv - 1) / kdiv;
         magic_s = (65536 + cs.stride - 1) / cs.stride;
         kc8 = (tid & 7) * 8;
         tap = (kbeg + kc8) / ch;
         c0 = (kbeg + kc8) - tap * ch;
-        const int gw = DGRAD ? cs.W : cs.Wo, gh = DGRAD ? cs.H : cs.Ho;
+        // rows: output pixels, input pixels, or the input pixels of one parity class
+        const int gw = !DGRAD ? cs.Wo : cls ? class_extent(cs.W, cs.cx, cs.stride) : cs.W;
+        const int gh = !DGRAD ? cs.Ho : cls ? class_extent(cs.H, cs.cy, cs.stride) : cs.H;
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             int c = tid + i * NT;
@@ -216,12 +225,17 @@ struct ConvRowsTile {
             int q = row / gw;
             py[i] = q % gh;
             img[i] = q / gh;
+            if (cls) {
+                px[i] = px[i] * cs.stride + cs.cx;
+                py[i] = py[i] * cs.stride + cs.cy;
+            }
         }
     }
     __device__ __forceinline__ void load(int d, int k0, int kend, int tid)
     {
         const int sh = DGRAD ? cs.Ho : cs.H, sw = DGRAD ? cs.Wo : cs.W;
-        const int u = small_div(tap, magic), v = tap - u * cs.k;
+        const int tq = small_div(tap, magic);
+        const int u = u0 + ustep * tq, v = v0 + ustep * (tap - tq * kdiv);
         const bool kin = k0 + kc8 < kend;
 #pragma unroll
         for (int i = 0; i < CH; ++i)
@@ -280,6 +294,7 @@ struct ConvKmTile {
     // k of the next load, per chunk.  DGRAD: (tap, o) in s1, s0.  WGRAD: output pixel as (n, y, x) in s2, s1, s0.
     int s0[CH], s1[CH], s2[CH], kk[CH];
     int d0, d1, d2;           // BK in the same mixed radix
+    int ntaps, nv, magic_nv, u0, v0, ustep;   // DGRAD: the taps K runs over (all, or those of a parity class)
     bool ok[DEPTH][CH];
     u32x4 st[DEPTH][CH];
 
@@ -296,6 +311,13 @@ struct ConvKmTile {
             d2 = 0;
             d1 = BK / cs.O;
             d0 = BK - d1 * cs.O;
+            const ClassTaps cu = class_taps(cs.cy, cs.pad, cs.stride, cs.k), cv = class_taps(cs.cx, cs.pad, cs.stride, cs.k);
+            nv = cs.cls ? cv.count : cs.k;
+            ntaps = (cs.cls ? cu.count : cs.k) * nv;
+            magic_nv = (65536 + nv - 1) / nv;
+            u0 = cs.cls ? cu.first : 0;
+            v0 = cs.cls ? cv.first : 0;
+            ustep = cs.cls ? cs.stride : 1;
         }
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
@@ -339,7 +361,9 @@ struct ConvKmTile {
                     int n = min(s2[i], cs.N - 1);           // pixels past the last one (tail of K) stay in the tensor
                     off = ((int64_t)(n * cs.H + yy) * cs.W + xx) * cs.I + c0[i];
                 } else {
-                    int tap = min(s1[i], cs.k * cs.k - 1);  // likewise for taps past the last one
+                    const int t = min(s1[i], ntaps - 1);     // likewise for taps past the last one
+                    const int tq = small_div(t, magic_nv);
+                    const int tap = (u0 + ustep * tq) * cs.k + v0 + ustep * (t - tq * nv);
                     off = ((int64_t)s0[i] * cs.k * cs.k + tap) * cs.I + c0[i];
                 }
                 ok[d][i] = inside && colok[i] && kin;
@@ -427,10 +451,10 @@ constexpr int gemm2_lds_bytes()
 // lane to global memory, with the optional GELU epilogue.  Results (and the pre-activation the
 // gradient epilogue reads) are streamed with non-temporal accesses: 10 % faster on the wide products.  Every wave must be past its last read
 // of the operand tiles in LDS (the staging tile overlays them); ends without a barrier.
-template <int BM, int BN, int WGM, int WGN, int TM, int TN>
+template <int BM, int BN, int WGM, int WGN, bool MAPROWS, int TM, int TN>
 __device__ __forceinline__ void store_bf16_tile(const f32x16 (&acc)[TM][TN], bf16_t* lds, bf16_t* __restrict__ out, int64_t ldc,
                                                 const float* __restrict__ bias, int M, int N, int m0, int n0, int epilogue,
-                                                bf16_t* __restrict__ aux, int64_t ldaux, int tid)
+                                                bf16_t* __restrict__ aux, int64_t ldaux, int tid, const ConvShape& cs)
 {
     constexpr int NT = 64 * WGM * WGN;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
@@ -478,13 +502,21 @@ __device__ __forceinline__ void store_bf16_tile(const f32x16 (&acc)[TM][TN], bf1
         int m = m0 + ml, n = n0 + cc * 8;
         const bool ok = m < M && n < N;   // N is a multiple of 8 on this path
         u32x4 v = *reinterpret_cast<const u32x4*>(lds + ml * LDC + cc * 8);
+        int64_t mrow = m;
+        if (MAPROWS && cs.cls) {
+            // row m counts the input pixels of one parity class: its place among all input pixels
+            const int gw = class_extent(cs.W, cs.cx, cs.stride), gh = class_extent(cs.H, cs.cy, cs.stride);
+            const int mm = min(m, M - 1);
+            const int ix = mm % gw, q = mm / gw;
+            mrow = ((int64_t)(q / gh) * cs.H + (q % gh) * cs.stride + cs.cy) * cs.W + ix * cs.stride + cs.cx;
+        }
         if (epilogue == EPI_ACT_GRAD) {
             bf16x8 c8 = __builtin_bit_cast(bf16x8, v);
 #pragma unroll
             for (int e = 0; e < 8; ++e) c8[e] = (bf16_t)((float)c8[e] * gelu_grad_f((float)z8[q][e]));
             v = __builtin_bit_cast(u32x4, c8);
         }
-        if (ok) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + (int64_t)m * ldc + n));
+        if (ok) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + mrow * ldc + n));
         if (epilogue == EPI_ACT_STORE) {
             bf16x8 c8 = __builtin_bit_cast(bf16x8, v);
 #pragma unroll
@@ -510,7 +542,21 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm2_kernel(Operand A, Ope
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
     const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
-    const int kbeg = blockIdx.z * k_per_split;
+    int kbeg = blockIdx.z * k_per_split;
+    if constexpr (G == GATHER_CONV_DGRAD) {
+        if (cs.cls) {
+            // all parity classes of a strided data gradient in one launch: blockIdx.z is the class,
+            // each with its own number of rows and taps; K is not sliced
+            cs.cy = blockIdx.z / cs.stride;
+            cs.cx = blockIdx.z - cs.cy * cs.stride;
+            M = cs.N * class_extent(cs.H, cs.cy, cs.stride) * class_extent(cs.W, cs.cx, cs.stride);
+            K = class_taps(cs.cy, cs.pad, cs.stride, cs.k).count * class_taps(cs.cx, cs.pad, cs.stride, cs.k).count * cs.O;
+            A.rows = M;
+            kbeg = 0;
+            k_per_split = K;
+            if (m0 >= M) return;
+        }
+    }
     const int kend = min(K, kbeg + k_per_split);
     const int nk = (kend - kbeg + BK - 1) / BK;
 
@@ -611,8 +657,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm2_kernel(Operand A, Ope
                 }
         }
     } else {
-        store_bf16_tile<BM, BN, WGM, WGN>(acc, lds, reinterpret_cast<bf16_t*>(C), ldc, bias, M, N, m0, n0, epilogue, aux, ldaux,
-                                          tid);
+        store_bf16_tile<BM, BN, WGM, WGN, G == GATHER_CONV_DGRAD>(acc, lds, reinterpret_cast<bf16_t*>(C), ldc, bias, M, N, m0, n0,
+                                                                  epilogue, aux, ldaux, tid, cs);
     }
 }
 
@@ -643,6 +689,7 @@ hipError_t launch(const MatOp& op, const Operand& A, const Operand& B, hipStream
     float* partial = splits > 1 ? op.partial : nullptr;
     if (sizeof(OutT) == 4 && !op.out_f32 && !partial) return hipErrorInvalidValue;   // fp32 tiles need the reduce to reach a bf16 C
     dim3 grid((unsigned)ceil_div(op.M, BM), (unsigned)ceil_div(op.N, BN), (unsigned)splits);
+    if (G == GATHER_CONV_DGRAD && op.cs.cls) grid.z = (unsigned)(op.cs.stride * op.cs.stride);   // one slab of workgroups per parity class
     hipLaunchKernelGGL(kern, grid, dim3(NT), lds_bytes, st, A, B, op.cs, (OutT*)op.C, op.ldc, op.bias, partial, (int)op.M,
                        (int)op.N, (int)op.K, kps, op.epilogue, (bf16_t*)op.aux, op.ldaux);
     hipError_t e = hipGetLastError();
@@ -738,8 +785,26 @@ hipError_t mfma_gemm2(const MatOp& op, hipStream_t st)
         return by_tile<false, false, bf16_t, GATHER_CONV_FWD>(op, A, B, st);
     }
     if (op.gather == GATHER_CONV_DGRAD) {
-        Operand A{(const bf16_t*)op.A, 0, (int)op.M};
         Operand B{(const bf16_t*)op.B, 0, (int)op.N};
+        const ConvShape& cs = op.cs;
+        if (cs.stride > 1 && cs.k >= cs.stride) {
+            // Strided: an input pixel hears from an output pixel only through the taps of its parity
+            // class, 1 / stride^2 of them on average.  One product per class, over those taps only,
+            // written to the class's pixels (as one product over all taps, three quarters of a
+            // stride-2 gradient's multiplications are by zeros).
+            // The launch is shaped for class (0, 0), which has the most rows; the kernel takes the class
+            // from blockIdx.z and works out that class's rows and taps itself.
+            MatOp sub = op;
+            sub.cs.cls = 1;
+            sub.splits = 1;
+            sub.M = (int64_t)cs.N * class_extent(cs.H, 0, cs.stride) * class_extent(cs.W, 0, cs.stride);
+            int taps = 0;
+            for (int c = 0; c < cs.stride; ++c) taps = std::max(taps, class_taps(c, cs.pad, cs.stride, cs.k).count);
+            sub.K = (int64_t)taps * taps * cs.O;
+            Operand A{(const bf16_t*)op.A, 0, (int)sub.M};
+            return by_tile<false, true, bf16_t, GATHER_CONV_DGRAD>(sub, A, B, st);
+        }
+        Operand A{(const bf16_t*)op.A, 0, (int)op.M};
         return by_tile<false, true, bf16_t, GATHER_CONV_DGRAD>(op, A, B, st);
     }
     if (op.gather == GATHER_CONV_WGRAD) {

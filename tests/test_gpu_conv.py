@@ -66,6 +66,10 @@ def test_small_tucker_all_masks(dt):
     (2, 11, 9, 24, 16, 16, 8, 5, 1, 2),      # 5x5 core, channel counts on the 16-byte path
     (1, 16, 16, 8, 16, 8, 8, 7, 2, 3),       # 7x7 stride 2 pad 3 (stem geometry), 16-byte path
     (1, 20, 20, 3, 16, 3, 8, 7, 2, 3),       # the same with 3 input channels
+    (2, 13, 11, 16, 24, 8, 16, 3, 2, 1),     # stride 2 on odd image sizes (parity classes of unequal size)
+    (1, 14, 15, 16, 16, 8, 8, 3, 3, 1),      # stride 3: one tap per class
+    (2, 9, 10, 16, 16, 8, 8, 5, 2, 2),       # 5x5 stride 2: 3 or 2 taps per class and direction
+    (1, 6, 5, 16, 16, 8, 8, 3, 2, 0),        # stride 2 without padding
 ])
 def test_tucker_geometries(dt, geo):
     run_tucker(*geo, dt, 0, seed=sum(geo))
