@@ -175,3 +175,39 @@ def test_core_layer_full_size_sampled_bf16(C, hw):
     check(host(gW), oracle.conv_wgrad(dYo, Xo, k, 1, 1), "bf16", "dW")
     rest = [n for n in range(N) if n not in picks]
     assert torch.all(gX[rest] == 0), "input gradient of an image whose output gradient is zero"
+
+
+@pytest.mark.parametrize("C,hw", [(64, 56), (128, 28)])
+def test_tucker_stage_full_size_sampled_bf16(C, hw):
+    """A whole Tucker layer of the first two ResNet stages at full size (128 images, ranks C / 2), forward
+    and backward with nothing frozen, as the layer tables time it.  The oracle evaluates sampled
+    images: Y, A, B and dX of those, and the three weight gradients of an output gradient that is
+    zero on every other image."""
+    N, k, r = 128, 3, C // 2
+    picks = [0, 5, 31, 64, 90, 127]
+    rng = si.rng_for(4, 950 + C)
+    X = si.gaussian((N, hw, hw, C), rng).astype(np.float32)
+    P1, G, P2 = si.direct_tucker_factors(C, C, k, r, r, rng)
+    dY = np.zeros((N, hw, hw, C), dtype=np.float32)
+    dY[picks] = si.gaussian((len(picks), hw, hw, C), rng)
+    g = lrd.conv_geom(N, hw, hw, C, C, r, r, k, 1, 1)
+    X_, P1_, G_, P2_, dY_ = dev(X, "bf16"), dev(P1, "bf16"), dev(G, "bf16"), dev(P2, "bf16"), dev(dY, "bf16")
+    Y_, A_, B_ = empty((N, hw, hw, C), "bf16"), empty((N, hw, hw, r), "bf16"), empty((N, hw, hw, r), "bf16")
+    ws = workspace(lrd.tucker_conv_workspace_bytes(g, code("bf16"), 0))
+    lrd.tucker_conv_fwd(X_, P1_, G_, P2_, Y_, A_, B_, g, ws)
+    gX = empty((N, hw, hw, C), "bf16")
+    g1, gG, g2 = f32((r, C)), f32((r, k, k, r)), f32((C, r))
+    lrd.tucker_conv_bwd(dY_, X_, A_, B_, P1_, G_, P2_, gX, g1, gG, g2, 0, g, ws)
+    torch.cuda.synchronize()
+    Xo, P1o, Go, P2o, dYo = (seen(a, "bf16") for a in (X[picks], P1, G, P2, dY[picks]))
+    Ao, Bo, Yo = oracle.tucker_fwd(Xo, P1o, Go, P2o, 1, 1)
+    check(host(Y_[picks]), Yo, "bf16", "Y")
+    check(host(A_[picks]), Ao, "bf16", "A")
+    check(host(B_[picks]), Bo, "bf16", "B")
+    go = oracle.tucker_bwd(dYo, Xo, Ao, Bo, P1o, Go, P2o, 0, 1, 1)
+    check(host(gX[picks]), go["dX"], "bf16", "dX")
+    check(host(g1), go["dP1"], "bf16", "dP1")
+    check(host(gG), go["dG"], "bf16", "dG")
+    check(host(g2), go["dP2"], "bf16", "dP2")
+    rest = [n for n in range(N) if n not in picks]
+    assert torch.all(gX[rest] == 0), "input gradient of an image whose output gradient is zero"
