@@ -142,7 +142,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
 // The same sum for small fp32 results cut into many slices (weight gradients of narrow layers, whose
 // reduction runs over all pixels): one thread per output would leave most of the chip idle and walk
 // the slices one after the other, so LANES threads share a group of 4 outputs, thread l adds slices
-// l, l + LANES, ... in ascending order and the LANES sums are combined in ascending l.  Still a
+// l, l + LANES, ... in ascending order and the LANES sums are combined by a pairwise tree.  Still a
 // fixed order.
 template <int LANES, bool SGD = false>
 __global__ __launch_bounds__(256) void reduce_partials_wide_kernel(const float* __restrict__ partial, float* __restrict__ C,
@@ -159,10 +159,14 @@ __global__ __launch_bounds__(256) void reduce_partials_wide_kernel(const float* 
         for (int z = l; z < splits; z += LANES) s += *reinterpret_cast<const f32x4*>(partial + (int64_t)z * total + g * 4);
     part[l][gl] = s;
     __syncthreads();
-    if (l == 0 && g < groups) {
-        f32x4 t = part[0][gl];
+    // pairwise tree over the LANES sums (lane l takes in lane l + half): one fixed order again
 #pragma unroll
-        for (int q = 1; q < LANES; ++q) t += part[q][gl];
+    for (int half = LANES / 2; half >= 1; half /= 2) {
+        if (l < half) part[l][gl] += part[l + half][gl];
+        __syncthreads();
+    }
+    if (l == 0 && g < groups) {
+        const f32x4 t = part[0][gl];
         const int64_t i = g * 4;
         if constexpr (SGD) sgd_apply4(sgd, i, t);
         else *reinterpret_cast<f32x4*>(C + (i / N) * ldc + (i % N)) = t;
