@@ -75,6 +75,37 @@ hipError_t apply_epilogue(const MatOp& op, hipStream_t st)
     return hipSuccess;
 }
 
+size_t conv_dgrad_flip_bytes(const ConvShape& cs, bool bf16)
+{
+    if (!bf16 || cs.stride != 1 || cs.k < 2 || cs.pad > cs.k - 1 || cs.I % 8 != 0 || cs.O % 8 != 0) return 0;
+    return (size_t)cs.k * cs.k * cs.I * cs.O * 2;
+}
+
+namespace {
+// The data gradient of a stride-1 convolution as the forward convolution of dY [N][Ho][Wo][O] with
+// wt[i][k*k - 1 - t][o] = w[o][t][i] and padding k - 1 - pad.  False if this op is not one of those.
+bool conv_dgrad_as_fwd(const MatOp& op, MatOp* fwd)
+{
+    const ConvShape& cs = op.cs;
+    const size_t need = conv_dgrad_flip_bytes(cs, op.in_bf16);
+    if (op.gather != GATHER_CONV_DGRAD || op.out_f32 || !need || !op.scratch || op.scratch_bytes < need) return false;
+    if (reinterpret_cast<uintptr_t>(op.scratch) & 15u) return false;
+    MatOp f = op;
+    f.gather = GATHER_CONV_FWD;
+    f.cs.H = cs.Ho; f.cs.W = cs.Wo; f.cs.Ho = cs.H; f.cs.Wo = cs.W;
+    f.cs.I = cs.O; f.cs.O = cs.I;
+    f.cs.pad = cs.k - 1 - cs.pad;
+    f.B = op.scratch;
+    f.b_sn = (int64_t)cs.k * cs.k * cs.O;
+    f.b_sk = 1;
+    f.scratch = nullptr;
+    f.scratch_bytes = 0;
+    if (!mfma_gemm2_supported(f)) return false;
+    *fwd = f;
+    return true;
+}
+}  // namespace
+
 hipError_t run_matop(const MatOp& op_in, hipStream_t st)
 {
     MatOp op = op_in;
@@ -87,7 +118,12 @@ hipError_t run_matop(const MatOp& op_in, hipStream_t st)
     if (probed) (void)hipEventRecord(ev0, st);
     hipError_t e;
     bool epilogue_done = true;
+    MatOp flipped;
     if (conv_direct_supported(op)) e = conv_direct(op, st);
+    else if (conv_dgrad_as_fwd(op, &flipped)) {
+        e = flip_conv_weights(op.B, op.scratch, op.cs.O, op.cs.I, op.cs.k, st);
+        if (e == hipSuccess) e = mfma_gemm2(flipped, st);
+    }
     else if (mfma_gemm2_supported(op)) e = mfma_gemm2(op, st);
     else {
         epilogue_done = op.epilogue == EPI_NONE;

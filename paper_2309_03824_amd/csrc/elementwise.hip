@@ -207,6 +207,19 @@ __global__ __launch_bounds__(256) void sgd_step_kernel(float* __restrict__ w, fl
     }
 }
 
+// wt[i][k*k - 1 - t][o] = w[o][t][i]: the weights with which the data gradient of a stride-1
+// convolution is itself a forward convolution (of dY, with padding k - 1 - pad).
+__global__ __launch_bounds__(256) void flip_conv_weights_kernel(const bf16_t* __restrict__ w, bf16_t* __restrict__ wt, int O, int I,
+                                                                int kk)
+{
+    const int total = O * kk * I;
+    for (int e = blockIdx.x * 256 + threadIdx.x; e < total; e += gridDim.x * 256) {
+        const int i = e / (kk * O), rem = e - i * kk * O;
+        const int tf = rem / O, o = rem - tf * O;
+        wt[e] = w[((int64_t)o * kk + (kk - 1 - tf)) * I + i];
+    }
+}
+
 inline unsigned blocks_for(int64_t items)
 {
     int64_t b = ceil_div(items, 256);
@@ -253,6 +266,14 @@ hipError_t copy2d(const void* src, int64_t ld_src, int64_t rows_src, int64_t col
     else
         hipLaunchKernelGGL(copy2d_kernel<float>, grid, dim3(256), 0, st, (const float*)src, ld_src, rows_src, cols_src,
                            (float*)dst, ld_dst, rows_dst, cols_dst);
+    return hipGetLastError();
+}
+
+hipError_t flip_conv_weights(const void* w, void* wt, int O, int I, int k, hipStream_t st)
+{
+    const int64_t total = (int64_t)O * k * k * I;
+    if (total <= 0) return hipSuccess;
+    hipLaunchKernelGGL(flip_conv_weights_kernel, dim3(blocks_for(total)), dim3(256), 0, st, (const bf16_t*)w, (bf16_t*)wt, O, I, k * k);
     return hipGetLastError();
 }
 

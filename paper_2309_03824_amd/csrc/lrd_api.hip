@@ -690,8 +690,9 @@ size_t lrd_tucker_conv_workspace_bytes(const lrd_conv_geom* g, lrd_dtype dt, uin
     size_t part = std::max(std::max(partial_bytes(g->S, g->r2, pout, dt), partial_bytes(g->r2, kk * g->r1, pout, dt)),
                            partial_bytes(g->r1, g->C, pin, dt));
     part = std::max(part, round256(conv_direct_wgrad_bytes(cs, dt == LRD_BF16)));
-    // forward: A and B when not side-stored; backward: dA, dB, recomputed A and B, partials
-    return 2 * (a + b) + part;
+    // forward: A and B when not side-stored; backward: dA, dB, recomputed A and B, partials, and the
+    // flipped core weights of a stride-1 data gradient
+    return 2 * (a + b) + part + round256(conv_dgrad_flip_bytes(cs, dt == LRD_BF16));
 }
 
 lrd_status lrd_tucker_conv_fwd(const void* X, const void* P1, const void* G, const void* P2,
@@ -822,6 +823,8 @@ lrd_status lrd_tucker_conv_bwd(const void* dY, const void* X, const void* A, con
                             t1 ? partial_bytes(r1, C, pin, dt) : 0);
     if (tg) shared_bytes = std::max(shared_bytes, round256(conv_direct_wgrad_bytes(cs, dt == LRD_BF16)));
     if (shared_bytes) shared_partial = (float*)cv.take(shared_bytes);
+    const size_t flip_bytes = need_dA ? conv_dgrad_flip_bytes(cs, dt == LRD_BF16) : 0;
+    void* flip = flip_bytes ? cv.take(flip_bytes) : nullptr;
     if (!cv.ok) return LRD_ERR_WORKSPACE;
     if (t2) splits_for(w2);
     if (tg) {
@@ -836,6 +839,8 @@ lrd_status lrd_tucker_conv_bwd(const void* dY, const void* X, const void* A, con
         MatOp dg = nt(dB, r2, G, 0, dA, r1, pin, r1, kk * r2, dt, false);
         dg.gather = GATHER_CONV_DGRAD;
         dg.cs = cs;
+        dg.scratch = flip;
+        dg.scratch_bytes = flip_bytes;
         LRD_TRY(run_matop(dg, st));
     }
     if (dX) LRD_TRY(run_matop(nn(dA, r1, P1, C, dX, C, pin, C, r1, dt), st));
@@ -858,7 +863,8 @@ size_t lrd_dense_conv_workspace_bytes(const lrd_conv_geom* g, lrd_dtype dt)
     if (!dtype_ok(dt) || !geom_ok(g, false)) return 0;
     ConvShape cs = core_shape(*g, g->C, g->S);
     return std::max(partial_bytes(g->S, (int64_t)g->k * g->k * g->C, g->N * (int64_t)cs.Ho * cs.Wo, dt),
-                    round256(conv_direct_wgrad_bytes(cs, dt == LRD_BF16)));
+                    round256(conv_direct_wgrad_bytes(cs, dt == LRD_BF16))) +
+           round256(conv_dgrad_flip_bytes(cs, dt == LRD_BF16));
 }
 
 lrd_status lrd_dense_conv_fwd(const void* X, const void* W, void* Y, const lrd_conv_geom* g,
@@ -907,6 +913,9 @@ lrd_status lrd_dense_conv_bwd(const void* dY, const void* X, const void* W, void
         MatOp dg = nt(dY, g->S, W, 0, dX, g->C, pin, g->C, kk * g->S, dt, false);
         dg.gather = GATHER_CONV_DGRAD;
         dg.cs = cs;
+        dg.scratch_bytes = conv_dgrad_flip_bytes(cs, dt == LRD_BF16);
+        dg.scratch = dg.scratch_bytes ? cv.take(dg.scratch_bytes) : nullptr;
+        if (!cv.ok) return LRD_ERR_WORKSPACE;
         LRD_TRY(run_matop(dg, st));
     }
     if (dW) LRD_TRY(run_matop(wg, st));

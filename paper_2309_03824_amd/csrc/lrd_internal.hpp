@@ -55,7 +55,7 @@ struct MatOp {
     void* aux = nullptr;
     int64_t ldaux = 0;
     // Optional device scratch an engine may use (the direct convolution's weight gradient keeps
-    // its per-workgroup partial sums there).
+    // its per-workgroup partial sums there, a stride-1 data gradient its flipped weights).
     void* scratch = nullptr;
     size_t scratch_bytes = 0;
     // Optional optimizer step on the finished fp32 result (a dense weight gradient, ldc == N).
@@ -108,6 +108,11 @@ hipError_t copy2d(const void* src, int64_t ld_src, int64_t rows_src, int64_t col
                   int64_t rows_dst, int64_t cols_dst, int elem_bytes, hipStream_t st);
 hipError_t sgd_step(float* w, float* m, const float* g, void* copy, bool copy_bf16, int64_t n, float lr, float mu, float wd,
                     hipStream_t st);
+// wt [I][k][k][O] (bf16) = w [O][k][k][I] with the taps reversed: see conv_dgrad_as_fwd.
+hipError_t flip_conv_weights(const void* w, void* wt, int O, int I, int k, hipStream_t st);
+// Scratch bytes with which run_matop evaluates a stride-1 bf16 data gradient as a forward convolution
+// of dY with flipped weights (k-contiguous weights instead of transposing reads); 0 when it would not.
+size_t conv_dgrad_flip_bytes(const ConvShape& cs, bool bf16);
 // C = sum over split-K slices of partial[z][M][N], ascending z; C is fp32 or (c_bf16) bf16.
 // With `sgd` (fp32 results only) the sum is used for that step instead of being stored, when the
 // layout allows (then sgd->done is set).
