@@ -13,6 +13,11 @@
 // loop.  K-major operands are copied to LDS as they lie in memory and transposed by the LDS read
 // (ds_read_b64_tr_b16) when the MFMA fragments are fetched, so no layout costs a VALU instruction.
 // bf16 results leave through LDS so that each lane stores 16 contiguous bytes of an output row.
+//
+// Convolutions are the same kernel with gather tiles in place of the plain ones (implicit GEMM:
+// forward, data gradient, weight gradient).  The data gradient of a strided convolution runs as one
+// product per parity class of the input pixel (class = blockIdx.z), each over the taps that reach
+// its pixels, and writes its rows through a row map.
 #include <algorithm>
 
 #include "lrd_internal.hpp"
