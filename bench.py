@@ -281,6 +281,51 @@ def rank_sweep(args, torch, lrd):
                           points=points)))
 
 
+def train_step(args, torch, np, si, lrd, factorize):
+    """The FFN stack of the headline with the optimizer in the step: forward, then backward with the SGD
+    update (momentum 0.9, weight decay 1e-4; Section 4) of every factor the freeze mask leaves
+    trainable, through lrd_linear_bwd_sgd.  Replayed from captured graphs like the headline; beside
+    it the same step with nothing frozen, and forward + backward without any update.  Prints one JSON line."""
+    rank = lrd.quantize_rank(int(0.25 * min(D_MODEL, D_FF)), 64)
+    stack = Stack(lrd, torch, np, si, factorize, rank, seed_stream=0, true_svd=False)
+    opt = lrd.Sgd(1e-6, 0.9, 1e-4)
+    for blk in stack.layers:
+        for l in blk:
+            l["Um"], l["Vm"] = l["U"].float(), l["V"].float()
+            l["mU"], l["mV"] = torch.zeros_like(l["Um"]), torch.zeros_like(l["Vm"])
+    nbytes = max(lrd.linear_sgd_workspace_bytes(T_TOKENS, D_MODEL, D_FF, rank, lrd.BF16, 0),
+                 lrd.linear_sgd_workspace_bytes(T_TOKENS, D_FF, D_MODEL, rank, lrd.BF16, 0))
+    ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+
+    def backward_sgd(mask):
+        g = stack.X[N_BLOCKS]
+        for b in reversed(range(N_BLOCKS)):
+            l1, l2 = stack.layers[b]
+            out = stack.gX[b & 1]
+            lrd.linear_bwd_sgd(g, stack.A[b], l2["H"], l2["V"], l2["U"], stack.gZ, l2["Vm"], l2["Um"], l2["mV"], l2["mU"], None,
+                               mask, stack.Z[b], lrd.ACT_GELU, opt, ws)
+            lrd.linear_bwd_sgd(stack.gZ, stack.X[b], l1["H"], l1["V"], l1["U"], out if b > 0 else None, l1["Vm"], l1["Um"],
+                               l1["mV"], l1["mU"], None, mask, None, lrd.ACT_NONE, opt, ws)
+            g = out
+
+    def with_sgd(masks):
+        def run(parity):
+            stack.forward()
+            backward_sgd(masks[parity])
+        return run
+
+    alternating = (lrd.freeze_mask(lrd.KIND_SVD, 0), lrd.freeze_mask(lrd.KIND_SVD, 1))
+    res = dict(metric="FFN stack training step with the SGD update in the backward (ms per step, hip-graph replay)",
+               rank=rank, tokens=T_TOKENS, blocks=N_BLOCKS)
+    res["sequential_freezing_with_sgd_ms"] = graph_timed(torch, with_sgd(alternating), args.steps, args.warmup)
+    res["nothing_frozen_with_sgd_ms"] = graph_timed(torch, with_sgd((0, 0)), args.steps, args.warmup)
+    res["sequential_freezing_no_update_ms"] = graph_timed(torch, lambda parity: stack.step(alternating[parity]), args.steps, args.warmup)
+    res["nothing_frozen_no_update_ms"] = graph_timed(torch, lambda parity: stack.step(0), args.steps, args.warmup)
+    res["speedup_freezing_with_sgd"] = res["nothing_frozen_with_sgd_ms"] / res["sequential_freezing_with_sgd_ms"]
+    res["speedup_freezing_no_update"] = res["nothing_frozen_no_update_ms"] / res["sequential_freezing_no_update_ms"]
+    print(json.dumps(res), flush=True)
+
+
 def conv_stage(args, torch, lrd):
     """One 3x3 stage of config 4 (N = 128, Tucker ranks C/2) and the dense layer beside it: forward and
     the backward with nothing frozen, a few times, for a kernel trace.  Prints one JSON line."""
@@ -618,6 +663,8 @@ def main():
     ap.add_argument("--factorize", action="store_true", help="time the on-device factorization (SVD pairs, Tucker-2) instead")
     ap.add_argument("--layer-tables", action="store_true",
                     help="time the Tucker conv stages (config 4) and the transformer projections (config 5) instead")
+    ap.add_argument("--train-step", action="store_true",
+                    help="time the FFN stack with the SGD update inside the backward (lrd_linear_bwd_sgd) instead")
     ap.add_argument("--conv-stage", type=int, default=0, choices=(0, 64, 128, 256, 512),
                     help="run one 3x3 stage of config 4 (Tucker and dense, forward + backward) a few times, for a kernel trace")
     ap.add_argument("--sweep-step", type=int, default=16)
@@ -643,6 +690,9 @@ def main():
 
     if args.rank_sweep:
         rank_sweep(args, torch, lrd)
+        return
+    if args.train_step:
+        train_step(args, torch, np, si, lrd, factorize)
         return
     if args.conv_stage:
         conv_stage(args, torch, lrd)

@@ -16,5 +16,5 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 def test_help_lists_the_modes():
     p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--help"], capture_output=True, text=True, timeout=120)
     assert p.returncode == 0
-    for flag in ("--gpus", "--steps", "--warmup", "--rank-sweep", "--layer-tables", "--rank-search", "--factorize", "--conv-stage"):
+    for flag in ("--gpus", "--steps", "--warmup", "--rank-sweep", "--layer-tables", "--rank-search", "--factorize", "--train-step", "--conv-stage"):
         assert flag in p.stdout
