@@ -283,7 +283,7 @@ def rank_sweep(args, torch, lrd):
 
 def train_step(args, torch, np, si, lrd, factorize):
     """The FFN stack of the headline with the optimizer in the step: forward, then backward with the SGD
-    update (momentum 0.9, weight decay 1e-4; Section 4) of every factor the freeze mask leaves
+    update (momentum 0.9, weight decay 1e-4; Section 3) of every factor the freeze mask leaves
     trainable, through lrd_linear_bwd_sgd.  Replayed from captured graphs like the headline; beside
     it the same step with nothing frozen, and forward + backward without any update.  Prints one JSON line."""
     rank = lrd.quantize_rank(int(0.25 * min(D_MODEL, D_FF)), 64)

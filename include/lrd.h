@@ -17,8 +17,8 @@
  *     U [out x r]  applied second = the paper's decomposed layer L_r(1)
  *     H = X.V^T [T x r],  Y = H.U^T [T x out].
  * Tucker-2: P1 [r1 x C] = L_r(0), G [r2 x k x k x r1] = L_r(1) (core), P2 [S x r2] = L_r(2).
- * The one-time factorization that produces the factors (eq. 1, 2, 4) is a host step outside
- * this ABI.
+ * The one-time factorization that produces the factors (eq. 1, 2, 4) is lrd_svd_factors /
+ * lrd_tucker2_factors below.
  *
  * Conventions common to every device entry point
  *   - All matrix arguments are DEVICE pointers to dense row-major arrays whose leading dimension
@@ -111,7 +111,7 @@ lrd_status lrd_tucker_rank(int64_t C, int64_t S, int32_t k, double alpha, double
 int32_t lrd_svd_rank(int64_t in, int64_t out, double alpha);
 
 /*
- * Rank search of Algorithm 1 (Section 3.1, Rank Optimization) from measured step times.
+ * Rank search of Algorithm 1 (Section 2.1, Rank Optimization) from measured step times.
  *   times[i]  host array, step time of the layer decomposed at rank r_min + i, i = 0 .. r_max - r_min
  *             (any unit; the caller measures them, e.g. forward + backward through this library);
  *   t_dense   step time of the original layer in the same unit;
@@ -122,14 +122,16 @@ int32_t lrd_svd_rank(int64_t in, int64_t out, double alpha);
  *                          its neighbours d(r+1), d(r-1)  (the text's "first peak");
  *   LRD_SELECT_ARGMAX      the r with the largest d(r) > noise in the range, ties to the largest r
  *                          (the listing's arg max);
- * *r_opt = r - 1, the rank just below that drop, or r_max when there is none or when that rank is
- * not faster than r_max itself (the algorithm looks for a more efficient rank; an estimated rank
- * that is already aligned stays);
+ * *r_opt = r - 1, the rank just below that drop, or r_max when there is none;
  * *keep_decomposed = 1 iff t(*r_opt) < t_dense (otherwise the original layer is the faster one).
+ * mode is one of the two selections, optionally OR-ed with LRD_SELECT_REQUIRE_FASTER.  That flag is
+ * an extension the paper does not contain (a reading of the caption's "more efficient
+ * computations"): a pick whose time is not below t(r_max) is dropped and *r_opt = r_max, so that an
+ * estimated rank that is already aligned stays.  Without the flag the result is the literal one.
  * Pure host function.  LRD_ERR_INVALID_ARG for NULL pointers, an empty range, r_min < 1, negative
- * noise or non-finite times.
+ * noise, non-finite times or unknown mode bits.
  */
-enum { LRD_SELECT_FIRST_PEAK = 0, LRD_SELECT_ARGMAX = 1 };
+enum { LRD_SELECT_FIRST_PEAK = 0, LRD_SELECT_ARGMAX = 1, LRD_SELECT_REQUIRE_FASTER = 4 };
 lrd_status lrd_select_rank(const double* times, int32_t r_min, int32_t r_max, double t_dense, double noise,
                            int32_t mode, int32_t* r_opt, int32_t* keep_decomposed);
 
@@ -166,7 +168,7 @@ lrd_status lrd_linear_bwd(const void* dY, const void* X, const void* H, const vo
                           lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
- * Optimizer of the paper's experiments (Section 4: SGD, momentum 0.9, weight decay 1e-4), in the
+ * Optimizer of the paper's experiments (Section 3: SGD, momentum 0.9, weight decay 1e-4), in the
  * usual form g' = g + weight_decay * w;  m <- momentum * m + g';  w <- w - lr * m  (a momentum buffer
  * that starts at zero gives the customary first step m = g').
  *   w_master, momentum_buf  device fp32 [n], updated in place;  grad device fp32 [n];

@@ -128,8 +128,13 @@ def tucker_rank(C: int, S: int, k: int, alpha: float, beta: float = 1.0):
     return int(r1.value), int(r2.value)
 
 
+SELECT_REQUIRE_FASTER = 4
+
+
 def select_rank(times, r_min: int, r_max: int, t_dense: float, noise: float = 0.0, mode: int = 0):
-    """Algorithm 1's rank choice from measured times; returns (r_opt, keep_decomposed) or raises ValueError."""
+    """Algorithm 1's rank choice from measured times; returns (r_opt, keep_decomposed) or raises ValueError.
+    mode: 0 first peak (text), 1 arg max (listing); + SELECT_REQUIRE_FASTER for the extension that drops a
+    pick which is not faster than the estimated rank."""
     arr = (c_double * len(times))(*[float(v) for v in times])
     if len(times) != r_max - r_min + 1:
         raise ValueError("times must cover r_min..r_max")

@@ -127,25 +127,29 @@ int32_t lrd_ref_svd_rank(int64_t in, int64_t out, double alpha)
 }
 
 /*
- * Rank search of Algorithm 1 (Section 3.1, Rank Optimization), given the measured step times.
+ * Rank search of Algorithm 1 (Section 2.1, Rank Optimization), given the measured step times.
  * t[i] is the step time of the layer decomposed at rank r_min + i, i = 0 .. r_max - r_min;
  * t_dense the step time of the original layer.  The listing cannot be run as printed (it uses
  * t(r-1) before it is measured, and indexes the 257 -> 256 drop at 257 while the rank it wants
  * is 256), so this follows the text around it:
  *   d(r) = t(r) - t(r-1) for r in (r_min, r_max]  -- the first derivative of step time vs rank;
- *   mode 0 (text): going down from r_max, the first r whose d(r) exceeds `noise` and is not
+ *   selection 0 (text): going down from r_max, the first r whose d(r) exceeds `noise` and is not
  *                  smaller than its neighbours d(r+1), d(r-1) ("first peak");
- *   mode 1 (listing): the r with the largest d(r) over the whole range (ties: the largest r),
+ *   selection 1 (listing): the r with the largest d(r) over the whole range (ties: the largest r),
  *                  accepted only if d(r) exceeds `noise`;
- *   the rank just below that drop is the optimum, R_opt = r - 1; without such an r, or when that
- *   rank is not faster than the estimated one (an estimated rank that is already aligned), the
- *   estimated rank stays, R_opt = r_max;
+ *   the rank just below that drop is the optimum, R_opt = r - 1; without such an r the estimated
+ *   rank stays, R_opt = r_max;
  *   the decomposed layer is used iff t(R_opt) < t_dense.
+ * mode = selection, optionally + 4: an extension that is NOT in the paper's listing or text (one
+ * reading of the caption's "more efficient computations"): a pick that is not faster than the
+ * estimated rank itself is dropped and r_max stays.  Off unless the caller asks for it.
  * Returns 0, or -1 on invalid arguments (empty range, non-finite times, negative noise).
  */
 int32_t lrd_ref_select_rank(const double* t, int32_t r_min, int32_t r_max, double t_dense, double noise,
                             int32_t mode, int32_t* r_opt, int32_t* keep_decomposed)
 {
+    const int32_t require_faster = mode & 4;
+    mode &= ~4;
     if (!t || !r_opt || !keep_decomposed || r_min < 1 || r_max < r_min || (mode != 0 && mode != 1)) return -1;
     if (!(noise >= 0.0) || !isfinite(noise) || !isfinite(t_dense)) return -1;
     const int32_t n = r_max - r_min + 1;
@@ -178,9 +182,7 @@ int32_t lrd_ref_select_rank(const double* t, int32_t r_min, int32_t r_max, doubl
         }
     }
     *r_opt = found ? found - 1 : r_max;
-    /* the search is for a rank with "more efficient computations" than the estimated one (caption of
-     * Algorithm 1): a lower rank that is not faster than r_max only adds reconstruction error */
-    if (!(t[*r_opt - r_min] < t[r_max - r_min])) *r_opt = r_max;
+    if (require_faster && !(t[*r_opt - r_min] < t[r_max - r_min])) *r_opt = r_max;
     *keep_decomposed = t[*r_opt - r_min] < t_dense ? 1 : 0;
     return 0;
 }
@@ -490,7 +492,7 @@ void lrd_ref_tucker_bwd(const double* dY, const double* X, const double* A, cons
 }
 
 /* ------------------------------------------------------------------------------------------ */
-/* Optimizer step of the experiments (Section 4: SGD with momentum 0.9 and weight decay 1e-4)   */
+/* Optimizer step of the experiments (Section 3: SGD with momentum 0.9 and weight decay 1e-4)   */
 /* ------------------------------------------------------------------------------------------ */
 
 /*

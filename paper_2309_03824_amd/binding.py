@@ -233,7 +233,7 @@ def tucker2_factors(W, r1: int, r2: int, P1, G, P2, ws, stream=None) -> int:
     return int(sweeps.value)
 
 
-SELECT_FIRST_PEAK, SELECT_ARGMAX = 0, 1
+SELECT_FIRST_PEAK, SELECT_ARGMAX, SELECT_REQUIRE_FASTER = 0, 1, 4
 
 
 def select_rank(times, r_min: int, r_max: int, t_dense: float, noise: float = 0.0, mode: int = SELECT_FIRST_PEAK):

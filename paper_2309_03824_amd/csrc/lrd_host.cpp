@@ -89,6 +89,8 @@ lrd_status lrd_select_rank(const double* times, int32_t r_min, int32_t r_max, do
 {
     if (!times || !r_opt || !keep_decomposed) return LRD_ERR_INVALID_ARG;
     if (r_min < 1 || r_max < r_min) return LRD_ERR_INVALID_ARG;
+    const bool require_faster = (mode & LRD_SELECT_REQUIRE_FASTER) != 0;
+    mode &= ~int32_t(LRD_SELECT_REQUIRE_FASTER);
     if (mode != LRD_SELECT_FIRST_PEAK && mode != LRD_SELECT_ARGMAX) return LRD_ERR_INVALID_ARG;
     if (!std::isfinite(t_dense) || !std::isfinite(noise) || noise < 0.0) return LRD_ERR_INVALID_ARG;
     const size_t count = size_t(r_max - r_min) + 1;
@@ -112,7 +114,8 @@ lrd_status lrd_select_rank(const double* times, int32_t r_min, int32_t r_max, do
             if (slope[i] > noise && (pick < 0 || slope[i] > slope[pick])) pick = i;
     }
     int32_t chosen = pick < 0 ? r_max : r_min + (int32_t)pick;   // the rank just below the drop
-    if (times[chosen - r_min] >= times[count - 1]) chosen = r_max;  // not faster than the estimated rank: keep that one
+    // optional extension (not in the paper): a pick that is not faster than the estimated rank is dropped
+    if (require_faster && times[chosen - r_min] >= times[count - 1]) chosen = r_max;
     *r_opt = chosen;
     *keep_decomposed = times[chosen - r_min] < t_dense ? 1 : 0;
     return LRD_OK;

@@ -55,7 +55,8 @@ def test_rank_search_matches_oracle_bit_exact():
         times = [float(-(-r // m)) * rng.choice((1.0, 1.0, 1.25)) + rng.choice((0.0, 0.0, 0.01, 0.5)) for r in range(r_min, r_max + 1)]
         t_dense = rng.choice((0.5, 5.0, 50.0))
         noise = rng.choice((0.0, 0.05, 0.3, 2.0))
-        for mode in (lrd.SELECT_FIRST_PEAK, lrd.SELECT_ARGMAX):
+        for mode in (lrd.SELECT_FIRST_PEAK, lrd.SELECT_ARGMAX, lrd.SELECT_FIRST_PEAK | lrd.SELECT_REQUIRE_FASTER,
+                     lrd.SELECT_ARGMAX | lrd.SELECT_REQUIRE_FASTER):
             assert lrd.select_rank(times, r_min, r_max, t_dense, noise, mode) == oracle.select_rank(
                 times, r_min, r_max, t_dense, noise, mode), (times, r_min, noise, mode)
     for row in read_golden("alg1_rank_search.txt"):
@@ -63,7 +64,7 @@ def test_rank_search_matches_oracle_bit_exact():
         assert lrd.select_rank(times, int(row[1]), int(row[2]), float(row[4]), float(row[3]), int(row[0])) == (
             int(row[5]), bool(int(row[6])))
     for bad in (([1.0, 2.0], 0, 1, 1.0, 0.0, 0), ([1.0], 3, 3, 1.0, -1.0, 0), ([1.0, float("inf")], 3, 4, 1.0, 0.0, 0),
-                ([1.0], 3, 3, 1.0, 0.0, 2), ([1.0, 2.0], 3, 3, 1.0, 0.0, 0)):
+                ([1.0], 3, 3, 1.0, 0.0, 2), ([1.0], 3, 3, 1.0, 0.0, 8), ([1.0, 2.0], 3, 3, 1.0, 0.0, 0)):
         try:
             lrd.select_rank(*bad)
         except lrd.LrdError as e:

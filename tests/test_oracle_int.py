@@ -190,7 +190,8 @@ def test_alg1_invariances():
         times = [rng.choice((1.0, 1.25, 1.5, 2.0)) for _ in range(n)]
         t_dense = rng.choice((0.5, 1.3, 3.0))
         noise = rng.choice((0.0, 0.1, 0.3))
-        for mode in (0, 1):
+        for mode in (0, 1, 4, 5):
+            guarded, sel = bool(mode & 4), mode & 1
             base = oracle.select_rank(times, r_min, r_max, t_dense, noise, mode)
             # a constant offset on every time (dense included) and a common positive factor change nothing
             assert oracle.select_rank([t + 4.0 for t in times], r_min, r_max, t_dense + 4.0, noise, mode) == base
@@ -201,35 +202,44 @@ def test_alg1_invariances():
             d = {r: times[r - r_min] - times[r - 1 - r_min] for r in range(r_min + 1, r_max + 1)}
             big = [r for r in d if d[r] > noise]
             if r_opt == r_max:
-                # nothing chosen: no difference exceeds the noise (the largest one that does is always a local
-                # maximum), or the rank below the chosen drop is not faster than the estimated rank
-                if big:
-                    r_star = max(big, key=lambda r: (d[r], r)) if mode == 1 else next(
+                if not guarded:
+                    # literal reading: nothing chosen means no difference exceeds the noise (the largest one
+                    # that does is always a local maximum, so first-peak mode finds one whenever arg max does)
+                    assert not big
+                elif big:
+                    # extension: the rank below the chosen drop is not faster than the estimated rank
+                    r_star = max(big, key=lambda r: (d[r], r)) if sel == 1 else next(
                         r for r in sorted(big, reverse=True)
                         if d[r] >= d.get(r + 1, -math.inf) and d[r] >= d.get(r - 1, -math.inf))
                     assert not times[r_star - 1 - r_min] < times[-1]
             else:
-                assert times[r_opt - r_min] < times[-1]
+                if guarded:
+                    assert times[r_opt - r_min] < times[-1]
                 r_star = r_opt + 1
                 assert d[r_star] > noise
-                if mode == 1:
+                if sel == 1:
                     assert d[r_star] == max(d.values()) and all(d[r] < d[r_star] for r in d if r > r_star)
                 else:
                     assert d[r_star] >= d.get(r_star + 1, -math.inf) and d[r_star] >= d.get(r_star - 1, -math.inf)
                     for r in big:            # every higher candidate is beaten by a neighbour
                         if r > r_star:
                             assert d[r] < d.get(r + 1, -math.inf) or d[r] < d.get(r - 1, -math.inf)
+            if guarded:
+                # the flag only ever replaces a pick by r_max
+                plain = oracle.select_rank(times, r_min, r_max, t_dense, noise, sel)
+                assert base == plain or (r_opt == r_max and not times[plain[0] - r_min] < times[-1])
 
 
 def test_alg1_rejects_bad_arguments():
     import pytest
     for bad in (dict(times=[1.0, 2.0], r_min=0, r_max=1), dict(times=[1.0], r_min=3, r_max=3, noise=-1.0),
-                dict(times=[1.0, float("nan")], r_min=3, r_max=4), dict(times=[1.0], r_min=3, r_max=3, mode=2)):
+                dict(times=[1.0, float("nan")], r_min=3, r_max=4), dict(times=[1.0], r_min=3, r_max=3, mode=2),
+                dict(times=[1.0], r_min=3, r_max=3, mode=8), dict(times=[1.0], r_min=3, r_max=3, mode=6)):
         with pytest.raises(ValueError):
             oracle.select_rank(bad["times"], bad["r_min"], bad["r_max"], 1.0, bad.get("noise", 0.0), bad.get("mode", 0))
 
 
-# ---------------------------------------------------------------- optimizer step (Section 4: SGD, momentum 0.9, weight decay 1e-4)
+# ---------------------------------------------------------------- optimizer step (Section 3: SGD, momentum 0.9, weight decay 1e-4)
 def test_sgd_step_matches_the_library_optimizer():
     """Five steps against torch.optim.SGD on the CPU in fp64, momentum buffers starting at zero."""
     import numpy as np
