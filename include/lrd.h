@@ -28,8 +28,8 @@
  *     dtype LRD_F32: everything is fp32.
  *   - The caller owns every buffer, including the workspace `ws` (size from the matching
  *     *_workspace_bytes query; may be NULL when that query returns 0).  The library keeps no
- *     device memory; its only process-wide state is the tuning switch of lrd_set_fusion and
- *     the one-shot probe of lrd_profile_next.
+ *     device memory and the calls declared here keep no mutable state between calls (the
+ *     measurement aids of lrd_measure.h, a separate header, are the exception and say so).
  *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default stream).
  *     No call synchronises or allocates.
  *   - Arguments are validated on the host before anything is launched; on a non-OK status
@@ -299,36 +299,6 @@ lrd_status lrd_dense_conv_fwd(const void* X, const void* W, void* Y, const lrd_c
 lrd_status lrd_dense_conv_bwd(const void* dY, const void* X, const void* W, void* dX, float* dW,
                               const lrd_conv_geom* g, lrd_dtype dt, void* ws, size_t ws_bytes,
                               void* hip_stream);
-
-/*
- * Tuning switch for callers that measure: how a bf16 pair with r <= 256 is evaluated.
- * LRD_FUSION_AUTO (default) lets the library choose per shape; LRD_FUSION_ALWAYS keeps the rank-r
- * intermediate in LDS between the two products whenever the fused kernel supports the shape;
- * LRD_FUSION_NEVER runs two separate products through an intermediate in memory (H_save or the
- * workspace).  Results agree up to fp32 summation order.  Process-wide; returns the previous mode,
- * or -1 (and changes nothing) for an unknown mode.
- */
-enum { LRD_FUSION_AUTO = 0, LRD_FUSION_ALWAYS = 1, LRD_FUSION_NEVER = 2 };
-int32_t lrd_set_fusion(int32_t mode);
-
-/*
- * Profiling aid for callers that time individual kernels with HIP events.  Arms a one-shot
- * probe: the next matrix-product kernel the library launches in the given role is bracketed by
- * hipEventRecord(start) / hipEventRecord(stop) on the launch stream (both are caller-owned
- * hipEvent_t passed as void*).  The probe disarms itself after that launch; role 0 disarms.
- * With the fused pair kernel active, the DOWN roles bracket the fused kernel.  Not thread-safe
- * with respect to concurrent launches from other threads.
- */
-enum {
-    LRD_ROLE_NONE = 0,
-    LRD_ROLE_FWD_DOWN = 1,    /* H  = X.V^T   */
-    LRD_ROLE_FWD_UP = 2,      /* Y  = H.U^T   */
-    LRD_ROLE_DGRAD_UP = 3,    /* dH = dY.U    */
-    LRD_ROLE_DGRAD_DOWN = 4,  /* dX = dH.V    */
-    LRD_ROLE_WGRAD_U = 5,     /* dU = dY^T.H  */
-    LRD_ROLE_WGRAD_V = 6      /* dV = dH^T.X  */
-};
-lrd_status lrd_profile_next(int32_t role, void* start_event, void* stop_event);
 
 /* ------------------------------------------------------------------------------------------
  * One-time factorization on the device (Section 2: eq. 1, 2 truncated SVD; eq. 4 Tucker-2)

@@ -33,8 +33,11 @@ EXPORTS = (
     "lrd_dense_linear_workspace_bytes", "lrd_dense_linear_fwd", "lrd_dense_linear_bwd",
     "lrd_tucker_conv_workspace_bytes", "lrd_tucker_conv_fwd", "lrd_tucker_conv_bwd",
     "lrd_dense_conv_workspace_bytes", "lrd_dense_conv_fwd", "lrd_dense_conv_bwd",
-    "lrd_gelu_fwd", "lrd_gelu_bwd", "lrd_set_fusion", "lrd_profile_next",
+    "lrd_gelu_fwd", "lrd_gelu_bwd",
 )
+# measurement aids (include/lrd_measure.h): not part of the layer ABI
+MEASURE_EXPORTS = ("lrd_set_fusion", "lrd_profile_next", "lrd_measure_mfma_loop", "lrd_measure_stream")
+STREAM_READ, STREAM_WRITE, STREAM_COPY = 0, 1, 2
 
 
 class LrdError(RuntimeError):
@@ -134,6 +137,10 @@ def _load() -> ctypes.CDLL:
     lib.lrd_set_fusion.argtypes = [c_int32]
     lib.lrd_gelu_bwd.restype = ctypes.c_int
     lib.lrd_gelu_bwd.argtypes = [P, P, P, I64, ctypes.c_int, P]
+    lib.lrd_measure_mfma_loop.restype = ctypes.c_int
+    lib.lrd_measure_mfma_loop.argtypes = [P, c_int32, c_int32, POINTER(c_double), P]
+    lib.lrd_measure_stream.restype = ctypes.c_int
+    lib.lrd_measure_stream.argtypes = [P, P, SZ, c_int32, P]
     return lib
 
 
@@ -279,6 +286,18 @@ class HipEvent:
             HipEvent._hip.hipEventDestroy(self.handle)
         except Exception:
             pass
+
+
+def measure_mfma_loop(sink, workgroups: int, iters: int, stream=None) -> float:
+    """Launches the register-only matrix-instruction loop; returns the flops of the launch."""
+    assert sink.dtype == torch.float32 and sink.numel() >= workgroups * 256
+    fl = c_double(0.0)
+    _check(_lib.lrd_measure_mfma_loop(_ptr(sink), workgroups, iters, ctypes.byref(fl), _stream(stream)), "lrd_measure_mfma_loop")
+    return float(fl.value)
+
+
+def measure_stream(src, dst, nbytes: int, mode: int, stream=None):
+    _check(_lib.lrd_measure_stream(_ptr(src), _ptr(dst), nbytes, mode, _stream(stream)), "lrd_measure_stream")
 
 
 def profile_next(role: int, start: HipEvent = None, stop: HipEvent = None):

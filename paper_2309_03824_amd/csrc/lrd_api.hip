@@ -5,6 +5,7 @@
 
 #include "lrd.h"
 #include "lrd_internal.hpp"
+#include "lrd_measure.h"
 
 namespace lrd {
 namespace {

@@ -1,0 +1,163 @@
+"""GPU parity at the full sizes the benchmark times, in the launch configuration it times them in
+(default evaluation order, caller workspace from the size query), with a DENSE output gradient.
+
+The oracle cannot evaluate these layers whole in seconds, so each case uses what is exact on a part:
+  - rows of Y, H, dX depend on their own token (or image) only: the oracle runs on sampled tokens
+    (images) with the full factors;
+  - column j of dU and row j of dV depend on component j of the pair only (dU[:, j] = dY^T.H[:, j] with
+    H[:, j] = X.V[j]^T; dV[j] = (dY.U[:, j])^T.X): the oracle runs the pair restricted to sampled
+    components over ALL tokens, so the reduction over the tokens is checked on dense data;
+  - row o of a dense weight gradient depends on output o only: the oracle runs the layer restricted
+    to sampled outputs over all tokens.
+Convolution stages are small enough for the oracle to run whole (all 128 images)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as si
+from parity import check, dev, empty, f32, host, seen, workspace
+from paper_2309_03824_amd import binding as lrd
+
+pytestmark = pytest.mark.gpu
+DT = "bf16"
+
+
+def _rows(t, idx):
+    return host(t[torch.from_numpy(np.asarray(idx)).cuda()])
+
+
+def _linear_case(T, n_in, n_out, r, mask, seed, n_tok=96, n_comp=24):
+    rng = si.rng_for(3, seed)
+    X, dY = si.gaussian((T, n_in), rng), si.gaussian((T, n_out), rng)
+    U, V = si.direct_factors(n_out, n_in, r, rng)
+    tok = np.sort(rng.choice(T, size=n_tok, replace=False))
+    comp = np.sort(rng.choice(r, size=min(n_comp, r), replace=False))
+    X_, V_, U_, dY_ = dev(X, DT), dev(V, DT), dev(U, DT), dev(dY, DT)
+    Y_, H_ = empty((T, n_out), DT), empty((T, r), DT)
+    ws = workspace(lrd.linear_workspace_bytes(T, n_in, n_out, r, lrd.BF16, mask))
+    lrd.linear_fwd(X_, V_, U_, None, Y_, H_, ws)
+    gX, gV, gU = empty((T, n_in), DT), f32((r, n_in), -7.0), f32((n_out, r), -7.0)
+    lrd.linear_bwd(dY_, X_, H_, V_, U_, gX, gV, gU, None, mask, ws)
+    torch.cuda.synchronize()
+    Xo, Vo, Uo, dYo = seen(X, DT), seen(V, DT), seen(U, DT), seen(dY, DT)
+    # sampled tokens, full factors
+    Ho, Yo = oracle.linear_fwd(Xo[tok], Vo, Uo)
+    check(_rows(Y_, tok), Yo, DT, "Y rows")
+    check(_rows(H_, tok), Ho, DT, "H rows")
+    g = oracle.linear_bwd(dYo[tok], Xo[tok], Ho, Vo, Uo, 3)
+    check(_rows(gX, tok), g["dX"], DT, "dX rows")
+    # sampled components, all tokens, dense dY
+    Vs, Us = np.ascontiguousarray(Vo[comp]), np.ascontiguousarray(Uo[:, comp])
+    Hs, _ = oracle.linear_fwd(Xo, Vs, Us)
+    gs = oracle.linear_bwd(dYo, Xo, Hs, Vs, Us, mask, want_dX=False)
+    cidx = torch.from_numpy(comp).cuda()
+    if mask & 2:
+        assert torch.all(gU == -7.0)
+    else:
+        check(host(gU[:, cidx]), gs["dU"], DT, "dU columns")
+    if mask & 1:
+        assert torch.all(gV == -7.0)
+    else:
+        check(host(gV[cidx]), gs["dV"], DT, "dV rows")
+
+
+@pytest.mark.parametrize("r,mask", [(512, 1), (768, 0), (1024, 1), (1024, 2), (257, 0), (513, 1)])
+def test_rank_sweep_layer_full_size(r, mask):
+    """One 4096 x 4096 linear, 16384 tokens, at the ranks of the rank staircase beyond 256 (the widest
+    tiles, split reductions over all tokens) and at raw ranks next to them (padded-rank path)."""
+    _linear_case(16384, 4096, 4096, r, mask, seed=1000 + r)
+
+
+@pytest.mark.parametrize("n_in,n_out,mask", [(1024, 4096, 1), (4096, 1024, 2), (1024, 1024, 0)])
+def test_transformer_projections_full_size(n_in, n_out, mask):
+    """Encoder projections (hidden 1024, FFN 4096) at rank 256 on all 8192 tokens."""
+    _linear_case(8192, n_in, n_out, 256, mask, seed=2000 + n_in // 1024 + n_out // 512)
+
+
+@pytest.mark.parametrize("T,n_in,n_out", [(8192, 1024, 4096), (16384, 4096, 4096), (8192, 768, 3072)])
+def test_dense_linear_full_size(T, n_in, n_out):
+    """The undecomposed layer at the sizes it is timed at beside the decomposed ones."""
+    rng = si.rng_for(3, 7000 + n_out)
+    X, dY, W = si.gaussian((T, n_in), rng), si.gaussian((T, n_out), rng), si.linear_weight(n_out, n_in, rng)
+    tok = np.sort(rng.choice(T, size=64, replace=False))
+    outs = np.sort(rng.choice(n_out, size=24, replace=False))
+    X_, W_, dY_ = dev(X, DT), dev(W, DT), dev(dY, DT)
+    Y_ = empty((T, n_out), DT)
+    ws = workspace(lrd.dense_linear_workspace_bytes(T, n_in, n_out, lrd.BF16))
+    lrd.dense_linear_fwd(X_, W_, None, Y_, ws)
+    gX, gW = empty((T, n_in), DT), f32((n_out, n_in))
+    lrd.dense_linear_bwd(dY_, X_, W_, gX, gW, ws)
+    torch.cuda.synchronize()
+    Xo, Wo, dYo = seen(X, DT), seen(W, DT), seen(dY, DT)
+    check(_rows(Y_, tok), oracle.dense_linear_fwd(Xo[tok], Wo, None), DT, "Y rows")
+    dXo, _ = oracle.dense_linear_bwd(dYo[tok], Xo[tok], Wo)
+    check(_rows(gX, tok), dXo, DT, "dX rows")
+    _, dWo = oracle.dense_linear_bwd(np.ascontiguousarray(dYo[:, outs]), Xo, np.ascontiguousarray(Wo[outs]))
+    check(_rows(gW, outs), dWo, DT, "dW rows")
+
+
+def _conv_case(N, hw, C, S, r1, r2, k, stride, pad, mask, seed):
+    rng = si.rng_for(4, seed)
+    g = lrd.conv_geom(N, hw, hw, C, S, r1, r2, k, stride, pad)
+    ho, wo = g.out_hw()
+    X, dY = si.gaussian((N, hw, hw, C), rng), si.gaussian((N, ho, wo, S), rng)
+    P1, G, P2 = si.direct_tucker_factors(S, C, k, r1, r2, rng)
+    X_, P1_, G_, P2_, dY_ = (dev(a, DT) for a in (X, P1, G, P2, dY))
+    Y_, A_, B_ = empty((N, ho, wo, S), DT), empty((N, hw, hw, r1), DT), empty((N, ho, wo, r2), DT)
+    ws = workspace(lrd.tucker_conv_workspace_bytes(g, lrd.BF16, mask))
+    lrd.tucker_conv_fwd(X_, P1_, G_, P2_, Y_, A_, B_, g, ws)
+    gX = empty((N, hw, hw, C), DT)
+    g1, gG, g2 = f32((r1, C), -7.0), f32((r2, k, k, r1), -7.0), f32((S, r2), -7.0)
+    lrd.tucker_conv_bwd(dY_, X_, A_, B_, P1_, G_, P2_, gX, g1, gG, g2, mask, g, ws)
+    torch.cuda.synchronize()
+    Xo, P1o, Go, P2o, dYo = (seen(a, DT) for a in (X, P1, G, P2, dY))
+    Ao, Bo, Yo = oracle.tucker_fwd(Xo, P1o, Go, P2o, stride, pad)
+    check(host(Y_), Yo, DT, "Y")
+    check(host(A_), Ao, DT, "A")
+    check(host(B_), Bo, DT, "B")
+    go = oracle.tucker_bwd(dYo, Xo, Ao, Bo, P1o, Go, P2o, mask, stride, pad)
+    check(host(gX), go["dX"], DT, "dX")
+    for bit, name, got in ((1, "dP1", g1), (2, "dG", gG), (4, "dP2", g2)):
+        if mask & bit:
+            assert torch.all(got == -7.0), name
+        else:
+            check(host(got), go[name], DT, name)
+
+
+@pytest.mark.parametrize("C,hw,mask", [(256, 14, 0), (512, 7, 0), (256, 14, 2), (512, 7, 5), (64, 56, 0), (128, 28, 0)])
+def test_conv_stages_full_batch(C, hw, mask):
+    """ResNet-style 3x3 stages at N = 128 with Tucker ranks C/2, all images through the oracle."""
+    _conv_case(128, hw, C, C, C // 2, C // 2, 3, 1, 1, mask, seed=3000 + C + mask)
+
+
+@pytest.mark.parametrize("C,hw", [(64, 56), (128, 28), (256, 14)])
+def test_stride2_transitions_full_batch(C, hw):
+    """The stride-2 3x3 layers between the stages (C -> 2C, ranks C/2 and C) at N = 128."""
+    _conv_case(128, hw, C, 2 * C, C // 2, C, 3, 2, 1, 0, seed=3500 + C)
+
+
+@pytest.mark.parametrize("r", [309, 304, 256])
+def test_worked_example_layer(r):
+    """The [512,512,3,3] layer of Section 2.1 at the rank eq. 6 gives for 2x compression (309), the
+    aligned rank below it (304) and 256, on 7 x 7 maps, N = 128."""
+    _conv_case(128, 7, 512, 512, r, r, 3, 1, 1, 0, seed=3900 + r)
+
+
+def test_dense_conv_full_batch():
+    """The undecomposed 3x3 layer at two stage shapes, N = 128."""
+    for C, hw in ((256, 14), (512, 7)):
+        rng = si.rng_for(4, 4000 + C)
+        N, k = 128, 3
+        g = lrd.conv_geom(N, hw, hw, C, C, C // 2, C // 2, k, 1, 1)
+        X, dY, W = si.gaussian((N, hw, hw, C), rng), si.gaussian((N, hw, hw, C), rng), si.conv_weight(C, C, k, rng)
+        X_, W_, dY_ = dev(X, DT), dev(W, DT), dev(dY, DT)
+        Y_, gX, gW = empty((N, hw, hw, C), DT), empty((N, hw, hw, C), DT), f32((C, k, k, C))
+        ws = workspace(lrd.dense_conv_workspace_bytes(g, lrd.BF16))
+        lrd.dense_conv_fwd(X_, W_, Y_, g, ws)
+        lrd.dense_conv_bwd(dY_, X_, W_, gX, gW, g, ws)
+        torch.cuda.synchronize()
+        Xo, Wo, dYo = seen(X, DT), seen(W, DT), seen(dY, DT)
+        check(host(Y_), oracle.conv_fwd(Xo, Wo, 1, 1), DT, "Y")
+        check(host(gX), oracle.conv_dgrad(dYo, Wo, (hw, hw), 1, 1), DT, "dX")
+        check(host(gW), oracle.conv_wgrad(dYo, Xo, k, 1, 1), DT, "dW")

@@ -1,0 +1,85 @@
+"""Algorithm 1 (Section 2.1) end to end on the device: the step times of a small misaligned layer are
+measured through the library for every rank from the estimated one down to the lower bound, and the
+same measured curve is handed to the library's rank search and to the oracle's."""
+import pytest
+import torch
+
+import oracle
+from paper_2309_03824_amd import binding as lrd
+
+pytestmark = pytest.mark.gpu
+
+
+def _measure_curve(T, n_in, n_out, ranks, iters=6):
+    bf = torch.bfloat16
+    gen = torch.Generator(device="cuda").manual_seed(77)
+    X = torch.randn(T, n_in, device="cuda", generator=gen).to(bf)
+    dY = torch.randn(T, n_out, device="cuda", generator=gen).to(bf)
+    Y, dX = torch.empty(T, n_out, dtype=bf, device="cuda"), torch.empty(T, n_in, dtype=bf, device="cuda")
+    ws = torch.empty(max(lrd.linear_workspace_bytes(T, n_in, n_out, r, lrd.BF16, 0) for r in ranks) + 256,
+                     dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+    times = []
+    for r in ranks:
+        V = (torch.randn(r, n_in, device="cuda", generator=gen) * n_in ** -0.5).to(bf)
+        U = (torch.randn(n_out, r, device="cuda", generator=gen) * r ** -0.5).to(bf)
+        H = torch.empty(T, r, dtype=bf, device="cuda")
+        dV, dU = torch.empty(r, n_in, device="cuda"), torch.empty(n_out, r, device="cuda")
+
+        def step():
+            lrd.linear_fwd(X, V, U, None, Y, H, ws)
+            lrd.linear_bwd(dY, X, H, V, U, dX, dV, dU, None, 0, ws)
+        for _ in range(2):
+            step()
+        torch.cuda.synchronize()
+        best = float("inf")
+        for _ in range(3):
+            s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            s.record(stream)
+            for _ in range(iters):
+                step()
+            e.record(stream)
+            torch.cuda.synchronize()
+            best = min(best, s.elapsed_time(e) * 1e3 / iters)
+        times.append(best)
+    # the original layer
+    W = (torch.randn(n_out, n_in, device="cuda", generator=gen) * n_in ** -0.5).to(bf)
+    dW = torch.empty(n_out, n_in, device="cuda")
+    wsd = torch.empty(lrd.dense_linear_workspace_bytes(T, n_in, n_out, lrd.BF16) + 256, dtype=torch.uint8, device="cuda")
+
+    def dense():
+        lrd.dense_linear_fwd(X, W, None, Y, wsd)
+        lrd.dense_linear_bwd(dY, X, W, dX, dW, wsd)
+    for _ in range(2):
+        dense()
+    torch.cuda.synchronize()
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s.record(stream)
+    for _ in range(iters):
+        dense()
+    e.record(stream)
+    torch.cuda.synchronize()
+    return times, s.elapsed_time(e) * 1e3 / iters
+
+
+def test_rank_search_on_measured_times():
+    n_in = n_out = 512
+    alpha = 3.3
+    R, R_min = lrd.svd_rank(n_in, n_out, alpha), lrd.svd_rank(n_in, n_out, alpha + 1.0)
+    assert (R, R_min) == (oracle.svd_rank(n_in, n_out, alpha), oracle.svd_rank(n_in, n_out, alpha + 1.0))
+    assert R == 77 and R % 8 != 0 and R_min < 64 < R       # a misaligned estimate with aligned ranks inside the range
+    ranks = list(range(R_min, R + 1))
+    times, t_dense = _measure_curve(2048, n_in, n_out, ranks)
+    noise = 0.03 * sorted(times)[len(times) // 2]
+    picks = {}
+    for mode in (lrd.SELECT_FIRST_PEAK, lrd.SELECT_ARGMAX, lrd.SELECT_FIRST_PEAK | lrd.SELECT_REQUIRE_FASTER,
+                 lrd.SELECT_ARGMAX | lrd.SELECT_REQUIRE_FASTER):
+        got = lrd.select_rank(times, R_min, R, t_dense, noise, mode)
+        assert got == oracle.select_rank(times, R_min, R, t_dense, noise, mode), (mode, times)
+        picks[mode] = got
+    # a raw rank runs at the padded rank plus copies, so every drop of this library's curve sits just above
+    # a multiple of 8: whatever drop is picked, the rank below it is aligned (or nothing was picked)
+    for mode, (r_opt, _) in picks.items():
+        assert r_opt % 8 == 0 or r_opt == R, (mode, r_opt, times)
+    # with the noise floor above every difference nothing is a drop and the estimated rank stays
+    assert lrd.select_rank(times, R_min, R, t_dense, 10.0 * max(times), lrd.SELECT_FIRST_PEAK)[0] == R

@@ -15,12 +15,13 @@ from paper_2309_03824_amd import factorize
 
 
 def test_every_declared_symbol_is_exported():
-    header = open(os.path.join(ROOT, "include", "lrd.h")).read()
-    declared = set(re.findall(r"\b(lrd_[a-z0-9_]+)\s*\(", header))
-    assert declared == set(lrd.EXPORTS)
     lib = ctypes.CDLL(lrd.LIB_PATH)
-    for name in declared:
-        assert hasattr(lib, name), name
+    for fname, exports in (("lrd.h", lrd.EXPORTS), ("lrd_measure.h", lrd.MEASURE_EXPORTS)):
+        header = open(os.path.join(ROOT, "include", fname)).read()
+        declared = set(re.findall(r"\b(lrd_[a-z0-9_]+)\s*\(", header))
+        assert declared == set(exports), fname
+        for name in declared:
+            assert hasattr(lib, name), name
 
 
 def test_integer_rules_match_oracle_bit_exact():
