@@ -1,17 +1,26 @@
-"""Benchmark: one training step (forward + backward) of a 12-block encoder FFN stack whose
-linears are SVD-decomposed, rank-quantized and sequentially frozen, on one MI355X.
+"""Benchmark of the decomposed-layer forward + backward path on one MI355X.  Prints ONE JSON line.
 
-Workload (synthetic, seeded): 12 x {Linear 768->3072, GELU, Linear 3072->768}; every weight
-W ~ N(0, 1/fan_in) is decomposed by truncated SVD at rank 25% of min(in,out) = 192 (a multiple
-of 64); tokens = batch 32 x seq 256 = 8192, bf16 activations ~ N(0,1); the freeze mask of step s
-is Algorithm 2's mask for epoch s (V frozen on even steps, U frozen on odd steps).
+Headline workload (synthetic, seeded): the decomposed linear layers of a 12-layer transformer encoder,
+hidden 1024, FFN 4096, 8192 tokens (batch 16 x sequence 512), bf16.  Per layer: the query / key / value
+projections as one grouped call on the shared input (1024 -> 3 x 1024), the attention output projection
+(1024 -> 1024), the FFN up-projection (1024 -> 4096, GELU folded into the call) and down-projection
+(4096 -> 1024); every weight is an SVD pair at the quantized rank 256; the freeze mask of step s is
+Algorithm 2's mask for epoch s for every layer (first factors frozen on even steps, second factors on odd
+steps).  One step = forward through all 12 layers, then backward.  The attention itself (softmax(QK^T)V),
+layer norms and residual additions are unchanged by the method and are not run: each layer's attention
+output and the gradient reaching its Q / K / V outputs are fixed synthetic tensors of the right shape, so
+every decomposed-layer kernel runs at its real shape on its own buffers.
 
-Prints ONE JSON line.  `value` is the algorithmic TFLOP/s of the decomposed layers (FLOPs as
-masked by freezing; the GELU between the two linears is folded into the pair kernels' epilogues,
-its time is inside the step and it adds no FLOPs to the numerator), with
-all inputs resident in HBM before the timed region.  Extra fields: tokens/s, the dense
-(undecomposed) stack and the unquantized-rank/unfrozen stack timed in the same run, the roofline
-of the dominant kernel, and the CPU oracle's rate on a bounded sample.
+`value` is the algorithmic TFLOP/s of the decomposed layers (FLOPs as masked by freezing), all inputs
+resident in HBM before the timed region, the K timed steps replayed from two captured HIP graphs (even /
+odd mask) after each replay was checked bit for bit against eager launches.  Beside it: tokens/s, the
+fraction of the step's binding roof (per layer pass max(flops / MFMA peak, algorithmic bytes / HBM peak),
+summed), the roofline of the product kernel with the largest share of the step (timed with HIP events in
+an eager pass over the same K steps), peaks measured in the same run (register-only MFMA loop, plain
+stream kernel), the undecomposed encoder and the raw-rank / unfrozen pair stacks, the other workloads
+(12-block FFN stack at rank 192; one 4096 x 4096 layer at ranks 256 / 257 / 512 / 1024; four Tucker 3x3
+stages at N = 128) each with time, TFLOP/s and binding-roof fraction, and the CPU oracle on a bounded
+sample.  Other modes (see --help) print their own single JSON line.
 """
 from __future__ import annotations
 
@@ -25,13 +34,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
-T_TOKENS, D_MODEL, D_FF, N_BLOCKS = 8192, 768, 3072, 12
+T_TOKENS, D_MODEL, D_FF, N_BLOCKS = 8192, 768, 3072, 12            # FFN-stack workload (rank 192)
+ENC_T, ENC_D, ENC_FF, ENC_LAYERS, ENC_RANK = 8192, 1024, 4096, 12, 256   # encoder workload (headline)
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
-# HBM bytes per launch of the reported kernel, by role (2 = Y = H.U^T, 4 = dX = dH.V), from rocprofv3
-# FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (profiles/gemm2_ffn_stack_hbm_traffic.md).  Set to None whenever
-# that kernel or its tiling changes.
-GEMM2_SHORT_K_TRAFFIC_BYTES = {2: 65.9e6, 4: 67.9e6}
 
 
 def layer_flops(T, n_in, n_out, r, mask, want_dx=True):
@@ -80,22 +86,11 @@ class Stack:
         nbytes = max(lrd.linear_workspace_bytes(T, D_MODEL, D_FF, rank, lrd.BF16, 0),
                      lrd.linear_workspace_bytes(T, D_FF, D_MODEL, rank, lrd.BF16, 0))
         self.ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
-        self.probe = None     # optional {role: [(start_event, end_event), ...]} filled around the probed calls
-        self.event_pool = []  # events created ahead of the timed region
-
-    def _probe(self, role):
-        """Arms the library's one-shot event probe for the next product kernel in this role."""
-        if self.probe is not None:
-            pair = self.event_pool.pop() if self.event_pool else (self.lrd.HipEvent(), self.lrd.HipEvent())
-            self.lrd.profile_next(role, *pair)
-            self.probe.setdefault(role, []).append(pair)
 
     def forward(self):
         lrd = self.lrd
         for b, (l1, l2) in enumerate(self.layers):
-            self._probe(lrd.ROLE_FWD_UP)
             lrd.linear_fwd_act(self.X[b], l1["V"], l1["U"], None, self.Z[b], self.A[b], l1["H"], lrd.ACT_GELU, self.ws)
-            self._probe(lrd.ROLE_FWD_UP)
             lrd.linear_fwd(self.A[b], l2["V"], l2["U"], None, self.X[b + 1], l2["H"], self.ws)
 
     def backward(self, mask):
@@ -105,11 +100,8 @@ class Stack:
         for b in reversed(range(N_BLOCKS)):
             l1, l2 = self.layers[b]
             out = self.gX[b & 1]
-            self._probe(lrd.ROLE_DGRAD_DOWN)
             lrd.linear_bwd_act(g, self.A[b], l2["H"], l2["V"], l2["U"], self.gZ, l2["dV"], l2["dU"], None, mask,
                                self.Z[b], lrd.ACT_GELU, self.ws)
-            if b > 0:
-                self._probe(lrd.ROLE_DGRAD_DOWN)
             lrd.linear_bwd(self.gZ, self.X[b], l1["H"], l1["V"], l1["U"], out if b > 0 else None,
                            l1["dV"], l1["dU"], None, mask, self.ws)
             g = out
@@ -168,6 +160,200 @@ class DenseStack:
             g = out
 
 
+def linear_bytes(T, n_in, n_out, r, mask, want_dx=True, act_out=False, act_in=False):
+    """Algorithmic bytes of one decomposed bf16 layer, (forward, backward): activations and factors
+    read once, results written once; the rank-r intermediate H is written by the forward only when the
+    backward will need it (second factor trainable) and dH never leaves the chip; fp32 gradients of
+    the trainable factors written once.  act_out: the forward also writes the activation of its result
+    (folded GELU); act_in: the backward also reads the pre-activation of its input."""
+    e = 2
+    fwd = e * (T * n_in + T * n_out + r * (n_in + n_out))
+    if not mask & 2:
+        fwd += e * T * r
+    if act_out:
+        fwd += e * T * n_out
+    bwd = e * T * n_out + e * r * (n_in + n_out)
+    if want_dx:
+        bwd += e * T * n_in
+    if act_in and want_dx:
+        bwd += e * T * n_in
+    if not mask & 1:
+        bwd += e * T * n_in + 4 * r * n_in
+    if not mask & 2:
+        bwd += e * T * r + 4 * r * n_out
+    return fwd, bwd
+
+
+def roof_us(flops, nbytes):
+    """Lower bound of a pass in microseconds and which roof binds it."""
+    t_mfma, t_hbm = flops / (MFMA_BF16_PEAK_TFLOPS * 1e12) * 1e6, nbytes / (HBM_PEAK_GBS * 1e9) * 1e6
+    return max(t_mfma, t_hbm), ("mfma" if t_mfma >= t_hbm else "hbm")
+
+
+class Encoder:
+    """The decomposed linears of a 12-layer encoder (hidden 1024, FFN 4096), rank r; fwd/bwd through the library only."""
+
+    def __init__(self, lrd, torch, np, si, rank, seed_stream, layers=ENC_LAYERS, grouped=True):
+        self.lrd, self.torch, self.r, self.n_layers, self.grouped = lrd, torch, rank, layers, grouped
+        dev, bf = "cuda", torch.bfloat16
+        rng = si.rng_for(5, seed_stream)
+        T, d, ff = ENC_T, ENC_D, ENC_FF
+
+        def to_dev(a):
+            bits = si.bf16_bits(a).view(np.int16)
+            return torch.from_numpy(bits).to(dev).view(bf).reshape(a.shape)
+
+        def empty(*shape, dt=bf):
+            return torch.empty(shape, dtype=dt, device=dev)
+
+        def pair(n_out, n_in):
+            U, V = si.direct_factors(n_out, n_in, rank, rng)
+            return dict(U=to_dev(U), V=to_dev(V), H=empty(T, rank), dU=empty(n_out, rank, dt=torch.float32),
+                        dV=empty(rank, n_in, dt=torch.float32))
+
+        self.layers = []
+        for _ in range(layers):
+            qkv = [si.direct_factors(d, d, rank, rng) for _ in range(3)]
+            L = dict(o=pair(d, d), up=pair(ff, d), dn=pair(d, ff),
+                     qkv=dict(U=to_dev(np.stack([u for u, _ in qkv])), V=to_dev(np.concatenate([v for _, v in qkv], axis=0)),
+                              H=empty(T, 3 * rank), dU=empty(3, d, rank, dt=torch.float32), dV=empty(3 * rank, d, dt=torch.float32),
+                              Y=empty(3, T, d), Hs=None if grouped else [empty(T, rank) for _ in range(3)]),
+                     # stand-ins for what the (unchanged, not run) attention hands to and receives from these layers
+                     attn=to_dev(si.gaussian((T, d), rng)), dqkv=to_dev(si.gaussian((3, T, d), rng, 1e-2)),
+                     Xo=empty(T, d), Z=empty(T, ff), A=empty(T, ff))
+            self.layers.append(L)
+        self.X = [to_dev(si.gaussian((T, d), rng))] + [empty(T, d) for _ in range(layers)]
+        self.gX = [empty(T, d) for _ in range(2)]
+        self.gXo, self.gAttn, self.gZ = empty(T, d), empty(T, d), empty(T, ff)
+        self.gQ = None if grouped else [empty(T, d) for _ in range(3)]
+        nbytes = max(lrd.linear_workspace_bytes(T, d, d, rank, lrd.BF16, 0), lrd.linear_workspace_bytes(T, d, ff, rank, lrd.BF16, 0),
+                     lrd.linear_workspace_bytes(T, ff, d, rank, lrd.BF16, 0),
+                     lrd.linear_group_workspace_bytes(T, d, d, rank, 3, lrd.BF16, 0))
+        self.ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+
+    def forward(self):
+        lrd = self.lrd
+        for l, L in enumerate(self.layers):
+            q, o, up, dn = L["qkv"], L["o"], L["up"], L["dn"]
+            if self.grouped:
+                lrd.linear_group_fwd(self.X[l], q["V"], q["U"], None, q["Y"], q["H"], self.ws)
+            else:
+                for g in range(3):
+                    lrd.linear_fwd(self.X[l], q["V"][g * self.r:(g + 1) * self.r], q["U"][g], None, q["Y"][g], q["Hs"][g], self.ws)
+            lrd.linear_fwd(L["attn"], o["V"], o["U"], None, L["Xo"], o["H"], self.ws)
+            lrd.linear_fwd_act(L["Xo"], up["V"], up["U"], None, L["Z"], L["A"], up["H"], lrd.ACT_GELU, self.ws)
+            lrd.linear_fwd(L["A"], dn["V"], dn["U"], None, self.X[l + 1], dn["H"], self.ws)
+
+    def backward(self, mask):
+        """Loss 0.5 ||X_last||^2: the gradient entering the last layer is the stack's output."""
+        lrd = self.lrd
+        g = self.X[self.n_layers]
+        for l in reversed(range(self.n_layers)):
+            L = self.layers[l]
+            q, o, up, dn = L["qkv"], L["o"], L["up"], L["dn"]
+            out = self.gX[l & 1]
+            lrd.linear_bwd_act(g, L["A"], dn["H"], dn["V"], dn["U"], self.gZ, dn["dV"], dn["dU"], None, mask, L["Z"], lrd.ACT_GELU, self.ws)
+            lrd.linear_bwd(self.gZ, L["Xo"], up["H"], up["V"], up["U"], self.gXo, up["dV"], up["dU"], None, mask, self.ws)
+            lrd.linear_bwd(self.gXo, L["attn"], o["H"], o["V"], o["U"], self.gAttn, o["dV"], o["dU"], None, mask, self.ws)
+            if self.grouped:
+                lrd.linear_group_bwd(L["dqkv"], self.X[l], q["H"], q["V"], q["U"], out if l > 0 else None, q["dV"], q["dU"], None, mask, self.ws)
+            else:
+                # three separate layers; their input gradients are added afterwards (glue, not the library's)
+                for i in range(3):
+                    lrd.linear_bwd(L["dqkv"][i], self.X[l], q["Hs"][i], q["V"][i * self.r:(i + 1) * self.r], q["U"][i],
+                                   self.gQ[i] if l > 0 else None, q["dV"][i * self.r:(i + 1) * self.r], q["dU"][i], None, mask, self.ws)
+                if l > 0:
+                    self.torch.add(self.gQ[0], self.gQ[1], out=out)
+                    out.add_(self.gQ[2])
+            g = out
+
+    def step(self, mask):
+        self.forward()
+        self.backward(mask)
+
+    def passes(self, mask):
+        """(name, flops, algorithmic bytes) of every layer pass (forward + backward of one call site) of a step."""
+        T, d, ff, r = ENC_T, ENC_D, ENC_FF, self.r
+        out = []
+        for l in range(self.n_layers):
+            first = l == 0
+            # Q/K/V: three pairs sharing X (read once) and producing one dX (written once)
+            f, b = layer_flops(T, d, d, r, mask, want_dx=not first)
+            e = 2
+            by = e * T * d + 3 * e * (T * d + 2 * r * d)                      # forward: X, three results, three factor pairs
+            by += 3 * e * (T * d + 2 * r * d) + (0 if first else e * T * d)   # backward: three gradients in, factors, one dX out
+            if not mask & 1:
+                by += e * T * d + 3 * 4 * r * d                               # X again and the fp32 gradients of the first factors
+            if not mask & 2:
+                by += 2 * e * T * 3 * r + 3 * 4 * r * d                       # H saved and re-read, gradients of the second factors
+            out.append(("qkv", 3 * (f + b), by))
+            for name, n_in, n_out, ao, ai in (("o", d, d, False, False), ("up", d, ff, True, False), ("dn", ff, d, False, True)):
+                f, b = layer_flops(T, n_in, n_out, r, mask)
+                byf, byb = linear_bytes(T, n_in, n_out, r, mask, act_out=ao, act_in=ai)
+                out.append((name, f + b, byf + byb))
+        return out
+
+    def flops(self, mask):
+        return sum(f for _, f, _ in self.passes(mask))
+
+    def roof_us(self, mask):
+        return sum(roof_us(f, b)[0] for _, f, b in self.passes(mask))
+
+
+class DenseEncoder:
+    """The same layers undecomposed (the original network's linears)."""
+
+    def __init__(self, lrd, torch, np, si, layers=ENC_LAYERS):
+        self.lrd, self.n_layers = lrd, layers
+        dev, bf = "cuda", torch.bfloat16
+        rng = si.rng_for(5, 77)
+        T, d, ff = ENC_T, ENC_D, ENC_FF
+
+        def to_dev(a):
+            bits = si.bf16_bits(a).view(np.int16)
+            return torch.from_numpy(bits).to(dev).view(bf).reshape(a.shape)
+
+        def empty(*shape, dt=bf):
+            return torch.empty(shape, dtype=dt, device=dev)
+
+        self.layers = [dict(Wqkv=to_dev(si.linear_weight(3 * d, d, rng)), Wo=to_dev(si.linear_weight(d, d, rng)),
+                            Wup=to_dev(si.linear_weight(ff, d, rng)), Wdn=to_dev(si.linear_weight(d, ff, rng)),
+                            attn=to_dev(si.gaussian((T, d), rng)), dqkv=to_dev(si.gaussian((T, 3 * d), rng, 1e-2)),
+                            Yqkv=empty(T, 3 * d), Xo=empty(T, d), Z=empty(T, ff), A=empty(T, ff)) for _ in range(layers)]
+        self.dW = dict(qkv=empty(3 * d, d, dt=torch.float32), o=empty(d, d, dt=torch.float32), up=empty(ff, d, dt=torch.float32),
+                       dn=empty(d, ff, dt=torch.float32))
+        self.X = [to_dev(si.gaussian((T, d), rng))] + [empty(T, d) for _ in range(layers)]
+        self.gX = [empty(T, d) for _ in range(2)]
+        self.gXo, self.gAttn, self.gA, self.gZ = empty(T, d), empty(T, d), empty(T, ff), empty(T, ff)
+        nbytes = max(lrd.dense_linear_workspace_bytes(T, d, 3 * d, lrd.BF16), lrd.dense_linear_workspace_bytes(T, d, ff, lrd.BF16),
+                     lrd.dense_linear_workspace_bytes(T, ff, d, lrd.BF16))
+        self.ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+
+    def step(self, mask=0):
+        lrd = self.lrd
+        for l, L in enumerate(self.layers):
+            lrd.dense_linear_fwd(self.X[l], L["Wqkv"], None, L["Yqkv"], self.ws)
+            lrd.dense_linear_fwd(L["attn"], L["Wo"], None, L["Xo"], self.ws)
+            lrd.dense_linear_fwd(L["Xo"], L["Wup"], None, L["Z"], self.ws)
+            lrd.gelu_fwd(L["Z"], L["A"])
+            lrd.dense_linear_fwd(L["A"], L["Wdn"], None, self.X[l + 1], self.ws)
+        g = self.X[self.n_layers]
+        for l in reversed(range(self.n_layers)):
+            L = self.layers[l]
+            out = self.gX[l & 1]
+            lrd.dense_linear_bwd(g, L["A"], L["Wdn"], self.gA, self.dW["dn"], self.ws)
+            lrd.gelu_bwd(self.gA, L["Z"], self.gZ)
+            lrd.dense_linear_bwd(self.gZ, L["Xo"], L["Wup"], self.gXo, self.dW["up"], self.ws)
+            lrd.dense_linear_bwd(self.gXo, L["attn"], L["Wo"], self.gAttn, self.dW["o"], self.ws)
+            lrd.dense_linear_bwd(L["dqkv"], self.X[l], L["Wqkv"], out if l > 0 else None, self.dW["qkv"], self.ws)
+            g = out
+
+    def flops(self):
+        T, d, ff = ENC_T, ENC_D, ENC_FF
+        per = 6 * T * (3 * d * d + d * d + 2 * d * ff)
+        return self.n_layers * per - 2 * T * 3 * d * d          # layer 0 has no input gradient
+
+
 def timed(torch, fn, steps, warmup, first_step=0):
     for s in range(warmup):
         fn(s)
@@ -194,41 +380,51 @@ def graph_timed(torch, step_for_parity, steps, warmup):
     return timed(torch, lambda s: graphs[s & 1].replay(), steps, warmup)
 
 
-def cpu_baseline(np, si, oracle, rank):
-    """The fp64 oracle, as it stands, on one full step of the workload (all blocks, all tokens)."""
-    rng = si.rng_for(2, 99)
-    T = T_TOKENS
-    blocks = N_BLOCKS
-    X = si.round_bf16(si.gaussian((T, D_MODEL), rng))
-    fac = []
-    for _ in range(blocks):
-        fac.append([tuple(si.round_bf16(a) for a in si.direct_factors(D_FF, D_MODEL, rank, rng)),
-                    tuple(si.round_bf16(a) for a in si.direct_factors(D_MODEL, D_FF, rank, rng))])
+def cpu_baseline(np, si, oracle, rank, layers=6):
+    """The fp64 oracle, as it stands, on `layers` of the 12 encoder layers at all tokens (forward +
+    backward, first factors frozen), the same chain of layer calls as the device step."""
+    rng = si.rng_for(5, 99)
+    T, d, ff = ENC_T, ENC_D, ENC_FF
     mask = oracle.freeze_mask(oracle.KIND_SVD, 0)
+    rb = si.round_bf16
+
+    def pair(n_out, n_in):
+        U, V = si.direct_factors(n_out, n_in, rank, rng)
+        return rb(U), rb(V)
+
+    net = [dict(qkv=[pair(d, d) for _ in range(3)], o=pair(d, d), up=pair(ff, d), dn=pair(d, ff),
+                attn=rb(si.gaussian((T, d), rng)), dqkv=rb(si.gaussian((3, T, d), rng, 1e-2))) for _ in range(layers)]
+    x = rb(si.gaussian((T, d), rng))
     t0 = time.perf_counter()
     saved = []
-    x = X
-    for (U1, V1), (U2, V2) in fac:
-        H1, Z = oracle.linear_fwd(x, V1, U1)
-        A = oracle.gelu_fwd(Z)
-        H2, y = oracle.linear_fwd(A, V2, U2)
-        saved.append((x, H1, Z, A, H2))
+    for L in net:
+        hq = [oracle.linear_fwd(x, V, U)[0] for U, V in L["qkv"]]
+        ho, xo = oracle.linear_fwd(L["attn"], L["o"][1], L["o"][0])
+        hu, z = oracle.linear_fwd(xo, L["up"][1], L["up"][0])
+        a = oracle.gelu_fwd(z)
+        hd, y = oracle.linear_fwd(a, L["dn"][1], L["dn"][0])
+        saved.append((x, hq, ho, xo, hu, z, a, hd))
         x = y
     g = x
-    for ((U1, V1), (U2, V2)), (x0, H1, Z, A, H2) in zip(reversed(fac), reversed(saved)):
-        b2 = oracle.linear_bwd(g, A, H2, V2, U2, mask)
-        gz = oracle.gelu_bwd(b2["dX"], Z)
-        b1 = oracle.linear_bwd(gz, x0, H1, V1, U1, mask)
-        g = b1["dX"]
+    for l in reversed(range(layers)):
+        L = net[l]
+        x0, hq, ho, xo, hu, z, a, hd = saved[l]
+        gz = oracle.gelu_bwd(oracle.linear_bwd(g, a, hd, L["dn"][1], L["dn"][0], mask)["dX"], z)
+        gxo = oracle.linear_bwd(gz, xo, hu, L["up"][1], L["up"][0], mask)["dX"]
+        oracle.linear_bwd(gxo, L["attn"], ho, L["o"][1], L["o"][0], mask)
+        gx = 0.0
+        for (U, V), h, dy in zip(L["qkv"], hq, L["dqkv"]):
+            gx = gx + oracle.linear_bwd(dy, x0, h, V, U, mask)["dX"]
+        g = gx
     dt = time.perf_counter() - t0
     flops = 0
-    for _ in range(blocks):
-        for (n_in, n_out) in ((D_MODEL, D_FF), (D_FF, D_MODEL)):
+    for _ in range(layers):
+        for n_in, n_out, n in ((d, d, 4), (d, ff, 1), (ff, d, 1)):
             f, b = layer_flops(T, n_in, n_out, rank, mask)
-            flops += f + b
+            flops += n * (f + b)
     return dict(value=flops / dt / 1e12, unit="TFLOP/s", cores=oracle.threads(), kind="oracle",
-                sample=f"{blocks} of {N_BLOCKS} FFN blocks, all {T} tokens, fwd+bwd with V frozen, fp64; {dt:.1f} s",
-                tokens_per_s=T / (dt * N_BLOCKS / blocks))
+                sample=f"{layers} of {ENC_LAYERS} encoder layers, all {T} tokens, fwd+bwd with first factors frozen, fp64; {dt:.1f} s",
+                tokens_per_s=T / (dt * ENC_LAYERS / layers))
 
 
 def rank_sweep(args, torch, lrd):
@@ -657,6 +853,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-comparators", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
+    ap.add_argument("--no-workloads", action="store_true", help="skip the other workloads (FFN stack, rank sweep points, Tucker stages)")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the in-run peak measurements")
     ap.add_argument("--rank-sweep", action="store_true", help="run the rank sweep (config 3) instead of the FFN stack")
     ap.add_argument("--rank-search", action="store_true",
                     help="run Algorithm 1's rank search on measured step times (Tucker [512,512,3,3] and linear 4096^2) instead")
@@ -715,29 +913,113 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    rank = lrd.quantize_rank(int(0.25 * min(D_MODEL, D_FF)), 64)
-    stack = Stack(lrd, torch, np, si, factorize, rank, seed_stream=0, true_svd=True)
+    out = headline(args, torch, np, si, lrd)
+    print(json.dumps(out))
+
+
+def event_us(torch, fn, iters, warm=2):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s.record()
+    for _ in range(iters):
+        fn()
+    e.record()
+    torch.cuda.synchronize()
+    return s.elapsed_time(e) * 1e3 / iters
+
+
+def measure_peaks(torch, lrd):
+    """What this machine delivers, in this run, to a register-only loop of bf16 matrix instructions and
+    to a plain 16-byte-per-lane streaming kernel over 1 GiB (cold: far beyond every cache)."""
+    sink = torch.empty(4096 * 256, dtype=torch.float32, device="cuda")
+    res = {}
+    for wgs in (1024, 4096):
+        fl = [0.0]
+
+        def run():
+            fl[0] = lrd.measure_mfma_loop(sink, wgs, 2048)
+        us = event_us(torch, run, 3)
+        res[f"mfma_bf16_loop_tflops_{wgs}_workgroups"] = fl[0] / (us * 1e-6) / 1e12
+    n = 1 << 30
+    a = torch.empty(n, dtype=torch.uint8, device="cuda")
+    b = torch.empty(n, dtype=torch.uint8, device="cuda")
+    a.zero_()
+    for name, mode, moved in (("read", lrd.STREAM_READ, n), ("write", lrd.STREAM_WRITE, n), ("copy", lrd.STREAM_COPY, 2 * n)):
+        us = event_us(torch, lambda: lrd.measure_stream(a, b, n, mode), 5)
+        res[f"stream_{name}_gbs"] = moved / (us * 1e-6) / 1e9
+    res["note"] = ("measured in this run with the library's own measurement kernels (lrd_measure.h); published peaks used for "
+                   "the roofline fractions: 2500 TFLOP/s bf16 MFMA, 8000 GB/s HBM")
+    return res
+
+
+def kernel_roofline(rows):
+    """Roofline object of the product kernel with the largest total time among the logged launches."""
+    groups = {}
+    for r in rows:
+        groups.setdefault(r["kernel"], []).append(r)
+    name, grp = max(groups.items(), key=lambda kv: sum(r["us"] for r in kv[1]))
+    total_us = sum(r["us"] for r in grp)
+    flops = nbytes = 0.0
+    shapes = {}
+    for r in grp:
+        M, N, K = r["M"], r["N"], r["K"]
+        out_b = 4 if r["role"] in (5, 6) or "f32" in r["kernel"] else 2
+        nbytes += 2 * (M * K + N * K) + out_b * M * N + (2 * M * N if r["epilogue"] else 0)
+        flops += 2.0 * M * N * K
+        key = f"{M}x{N}x{K}" + ("+act" if r["epilogue"] else "")
+        shapes[key] = shapes.get(key, 0) + 1
+    t_mfma, t_hbm = flops / (MFMA_BF16_PEAK_TFLOPS * 1e12), nbytes / (HBM_PEAK_GBS * 1e9)
+    n = len(grp)
+    if t_hbm >= t_mfma:
+        ach = nbytes / (total_us * 1e-6) / 1e9
+        roof = dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS)
+    else:
+        ach = flops / (total_us * 1e-6) / 1e12
+        roof = dict(bound="mfma", achieved=ach, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s", frac=ach / MFMA_BF16_PEAK_TFLOPS)
+    roof.update(traffic=None, kernel=name, avg_us=total_us / n, launches=n, bytes_per_launch=nbytes / n, flops_per_launch=flops / n,
+                share_of_logged_time=total_us / sum(r["us"] for r in rows), shapes=shapes,
+                note="algorithmic bytes per launch = both operands read once + result written once (+ the activation tensor the "
+                     "epilogue writes or reads); duration from HIP events on the launch stream around every launch of this kernel "
+                     "in an eager pass over the timed steps")
+    by_kernel = {k: dict(launches=len(v), total_us=sum(r["us"] for r in v)) for k, v in groups.items()}
+    return roof, by_kernel
+
+
+def graph_or_eager(torch, step_for_parity, steps, warmup, use_graph):
+    if use_graph:
+        return graph_timed(torch, step_for_parity, steps, warmup)
+    return timed(torch, lambda s: step_for_parity(s & 1), steps, warmup)
+
+
+def headline(args, torch, np, si, lrd):
+    peaks = None if args.no_peaks else measure_peaks(torch, lrd)
+    rank = lrd.quantize_rank(ENC_RANK, 64)
+    enc = Encoder(lrd, torch, np, si, rank, seed_stream=0)
+    masks = (lrd.freeze_mask(lrd.KIND_SVD, 0), lrd.freeze_mask(lrd.KIND_SVD, 1))
 
     def one(s):
-        stack.step(lrd.freeze_mask(lrd.KIND_SVD, s))
+        enc.step(masks[s & 1])
 
     for s in range(args.warmup):
         one(s)
     torch.cuda.synchronize()
-    stack.event_pool = [(lrd.HipEvent(), lrd.HipEvent()) for _ in range(args.steps * 4 * N_BLOCKS)]
-    stack.probe = {}
-    t0 = time.perf_counter()
-    for s in range(args.steps):
-        one(s)
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    probe, stack.probe = stack.probe, None
+    # eager pass over the K steps with every product bracketed by events (kernel-level roofline)
+    per_step = 64 * ENC_LAYERS
+    with lrd.ProfileLog(per_step * args.steps) as log:
+        t0 = time.perf_counter()
+        for s in range(args.steps):
+            one(s)
+        torch.cuda.synchronize()
+        eager_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    rows = log.rows()
+    roofline, by_kernel = kernel_roofline(rows)
+    ms = eager_ms
 
-    eager_ms = ms
-
-    # The same K steps replayed from two captured HIP graphs (even / odd freeze mask): every kernel
-    # of the step still runs, only the ~140 per-kernel launch gaps go.  Each replay is first checked
-    # bit for bit against an eager step, with eager work between the replays.
+    # The same K steps replayed from two captured HIP graphs (even / odd freeze mask): every kernel of the
+    # step still runs, only the per-kernel launch gaps go.  Each replay is first checked bit for bit against
+    # an eager step, with eager work between the replays.
     graph_ok = False
     if not args.no_graph:
         try:
@@ -746,26 +1028,26 @@ def main():
             for parity in (0, 1):
                 g = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(g, stream=side):
-                    stack.step(lrd.freeze_mask(lrd.KIND_SVD, parity))
+                    enc.step(masks[parity])
                 graphs[parity] = g
             torch.cuda.synchronize()
 
             def snapshot():
-                l1, l2 = stack.layers[0]
-                return [t.clone() for t in (stack.X[N_BLOCKS], stack.gX[0], l1["dU"], l1["dV"], l2["dU"], l2["dV"])]
+                L = enc.layers[0]
+                return [t.clone() for t in (enc.X[enc.n_layers], enc.gX[1], L["up"]["dU"], L["up"]["dV"], L["qkv"]["dU"], L["qkv"]["dV"])]
 
             graph_ok = True
-            for rep in range(3):
+            for rep in range(2):
                 for parity in (0, 1):
                     one(parity)
                     torch.cuda.synchronize()
                     want = snapshot()
-                    for t in (stack.X[N_BLOCKS], stack.gX[0]):
+                    for t in (enc.X[enc.n_layers], enc.gX[1]):
                         t.zero_()
                     graphs[parity].replay()
                     torch.cuda.synchronize()
                     got = snapshot()
-                    # frozen factors' gradient buffers are not written in either mode, so all six compare equal
+                    # frozen factors' gradient buffers are not written in either mode, so all of them compare equal
                     graph_ok = graph_ok and all(torch.equal(a, b) for a, b in zip(want, got))
             if graph_ok:
                 for s in range(args.warmup):
@@ -776,79 +1058,154 @@ def main():
                     graphs[s & 1].replay()
                 torch.cuda.synchronize()
                 ms = (time.perf_counter() - t0) * 1e3 / args.steps
+            del graphs
         except Exception as exc:      # capture unsupported: keep the eager figure
             print(f"bench.py: graph replay skipped ({exc})", file=sys.stderr)
             graph_ok = False
 
-    flops_even, flops_odd = stack.flops(1), stack.flops(2)
     n_even = (args.steps + 1) // 2
-    flops = (flops_even * n_even + flops_odd * (args.steps - n_even)) / args.steps
+    flops = (enc.flops(masks[0]) * n_even + enc.flops(masks[1]) * (args.steps - n_even)) / args.steps
+    roof = (enc.roof_us(masks[0]) * n_even + enc.roof_us(masks[1]) * (args.steps - n_even)) / args.steps
     tflops = flops / (ms * 1e-3) / 1e12
-
-    # Dominant kernel by total time (see profiles/): the eight-wave 128x128-tile bf16 MFMA product kernel,
-    # which runs the two short-K products of a layer: Y = H.U^T in the forward (out = 3072 with the GELU
-    # epilogue, which writes the pre-activation and the activation; out = 768 without) and dX = dH.V in
-    # the backward (in = 3072 with the GELU-gradient epilogue, which reads the pre-activation; in = 768
-    # without).  Both roles are bracketed by HIP events inside the timed region through
-    # lrd_profile_next; the one with the larger total in this run is reported.
-    # Algorithmic bytes per launch, the same for both: the rank-r operand and the factor read once, the
-    # wide result written once, plus one more wide tensor (written activation / read pre-activation)
-    # under the epilogue, all bf16.
-    totals = {role: sum(s_.elapsed_us(e_) for s_, e_ in pairs) for role, pairs in probe.items()}
-    role = max(totals, key=totals.get)
-    k_us = totals[role] / len(probe[role])
-    k_bytes = (2 * (T_TOKENS * rank + D_FF * rank + 2 * T_TOKENS * D_FF) +
-               2 * (T_TOKENS * rank + D_MODEL * rank + T_TOKENS * D_MODEL)) / 2
-    if role == lrd.ROLE_DGRAD_DOWN:
-        # block 0's first layer needs no dX, so this role has one wide launch more than narrow ones
-        n_wide, n_narrow = N_BLOCKS, N_BLOCKS - 1
-        k_bytes = (n_wide * 2 * (T_TOKENS * rank + D_FF * rank + 2 * T_TOKENS * D_FF) +
-                   n_narrow * 2 * (T_TOKENS * rank + D_MODEL * rank + T_TOKENS * D_MODEL)) / (n_wide + n_narrow)
-    achieved = k_bytes / (k_us * 1e-6) / 1e9
-    name = {lrd.ROLE_FWD_UP: "gemm2_kernel<128,128,2,4,2,false,false,bf16> as Y = H.U^T (lrd_linear_fwd / lrd_linear_fwd_act)",
-            lrd.ROLE_DGRAD_DOWN: "gemm2_kernel<128,128,2,4,2,false,true,bf16> as dX = dH.V (lrd_linear_bwd / lrd_linear_bwd_act)"}[role]
-    roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved / HBM_PEAK_GBS,
-                    traffic=GEMM2_SHORT_K_TRAFFIC_BYTES[role] if GEMM2_SHORT_K_TRAFFIC_BYTES else None, kernel=name,
-                    avg_us=k_us, launches=len(probe[role]), bytes_per_launch=k_bytes)
-
-    out = dict(metric="decomposed-layer fwd+bwd throughput (12-block encoder FFN stack)", value=tflops,
-               unit="TFLOP/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms,
+    out = dict(metric="decomposed-layer fwd+bwd throughput (12-layer encoder, hidden 1024, FFN 4096, SVD rank 256: Q/K/V/O and FFN linears)",
+               value=tflops, unit="TFLOP/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms,
                higher_is_better=True, scaling="weak", vs_baseline=None, dtype="bf16", data="synthetic",
-               config=dict(workload="encoder FFN stack: 12 x (768->3072, GELU, 3072->768), SVD rank 192 (25%, multiple of 64), "
-                                    "8192 tokens (32 x 256), sequential freezing alternating V/U per step",
-                           tokens=T_TOKENS, rank=rank, blocks=N_BLOCKS),
-               tokens_per_s=T_TOKENS / (ms * 1e-3), frac_bf16_mfma_peak=tflops / MFMA_BF16_PEAK_TFLOPS,
+               config=dict(workload="config 5: 12-layer transformer encoder, hidden 1024, 16 heads, FFN 4096, seq 512 x batch 16 = 8192 tokens, "
+                                    "bf16; all Q/K/V/O and FFN linears SVD-decomposed at quantized rank 256, sequential freezing by step "
+                                    "parity; decomposed-linear kernels only (attention, layer norm, residuals not run)",
+                           tokens=ENC_T, rank=rank, layers=ENC_LAYERS, hidden=ENC_D, ffn=ENC_FF),
+               tokens_per_s=ENC_T / (ms * 1e-3), frac_bf16_mfma_peak=tflops / MFMA_BF16_PEAK_TFLOPS,
+               binding_roof=dict(roof_ms_per_step=roof * 1e-3, frac=roof * 1e-3 / ms,
+                                 note="sum over the layer passes of max(flops / 2500 TFLOP/s, algorithmic bytes / 8000 GB/s), over the measured step"),
                launch="hip-graph replay" if graph_ok else "eager", eager_ms_per_step=eager_ms,
-               roofline=roofline)
+               roofline=roofline, kernels=by_kernel)
+    if peaks is not None:
+        out["peaks"] = peaks
+    del enc
+    torch.cuda.empty_cache()
 
     if not args.no_comparators:
         # Every comparator is timed the way the headline is (graph replay when that worked, else eager),
         # so the ratios compare GPU work and not host launch overhead.
         k = max(4, args.steps // 2)
-        clock = (lambda fn: graph_timed(torch, fn, k, 2)) if graph_ok else (lambda fn: timed(torch, fn, k, 2))
-        dense = DenseStack(lrd, torch, np, si)
-        d_ms = clock(lambda s: dense.step())
+        dense = DenseEncoder(lrd, torch, np, si)
+        d_ms = graph_or_eager(torch, lambda parity: dense.step(), k, 2, graph_ok)
+        d_tflops = dense.flops() / (d_ms * 1e-3) / 1e12
         del dense
         torch.cuda.empty_cache()
-        raw_rank = rank - 1            # an unquantized rank next to it, nothing frozen: "vanilla" decomposition
-        vanilla = Stack(lrd, torch, np, si, factorize, raw_rank, seed_stream=1, true_svd=False)
-        v_ms = clock(lambda s: vanilla.step(0))
+        raw_rank = rank + 1            # the paper's own example of an unquantized rank (257 -> 256), nothing frozen
+        vanilla = Encoder(lrd, torch, np, si, raw_rank, seed_stream=1, grouped=False)
+        v_ms = graph_or_eager(torch, lambda parity: vanilla.step(0), k, 2, graph_ok)
         del vanilla
-        unfrozen = Stack(lrd, torch, np, si, factorize, rank, seed_stream=1, true_svd=False)
-        u_ms = clock(lambda s: unfrozen.step(0))
+        torch.cuda.empty_cache()
+        unfrozen = Encoder(lrd, torch, np, si, rank, seed_stream=1)
+        u_ms = graph_or_eager(torch, lambda parity: unfrozen.step(0), k, 2, graph_ok)
         del unfrozen
-        out["comparators"] = dict(dense_ms_per_step=d_ms, dense_tflops=12 * 6 * T_TOKENS * D_MODEL * D_FF * 2 / (d_ms * 1e-3) / 1e12,
+        torch.cuda.empty_cache()
+        out["comparators"] = dict(dense_ms_per_step=d_ms, dense_tflops=d_tflops, dense_frac_bf16_mfma_peak=d_tflops / MFMA_BF16_PEAK_TFLOPS,
                                   speedup_vs_dense=d_ms / ms,
-                                  vanilla_rank=raw_rank, vanilla_unfrozen_ms_per_step=v_ms,
-                                  quantized_unfrozen_ms_per_step=u_ms,
-                                  speedup_rank_quantization=v_ms / u_ms, speedup_freezing=u_ms / ms,
-                                  speedup_combined=v_ms / ms,
-                                  note="comparators are launched the same way as the headline (%s)"
-                                       % ("hip-graph replay" if graph_ok else "eager"))
+                                  vanilla_rank=raw_rank, vanilla_unfrozen_ms_per_step=v_ms, quantized_unfrozen_ms_per_step=u_ms,
+                                  speedup_rank_quantization=v_ms / u_ms, speedup_freezing=u_ms / ms, speedup_combined=v_ms / ms,
+                                  note="vanilla = raw rank 257 (Section 2.1's 257 -> 256 example), nothing frozen, Q/K/V as three separate layers; comparators are "
+                                       "launched the same way as the headline (%s)" % ("hip-graph replay" if graph_ok else "eager"))
+    if not args.no_workloads:
+        out["workloads"] = other_workloads(args, torch, np, si, lrd, graph_ok)
     if not args.no_cpu_baseline:
         import oracle
         out["cpu_baseline"] = cpu_baseline(np, si, oracle, rank)
-    print(json.dumps(out))
+    return out
+
+
+def other_workloads(args, torch, np, si, lrd, graph_ok):
+    """The remaining workloads, each with time, TFLOP/s and fraction of its binding roof."""
+    from paper_2309_03824_amd import factorize
+    res = {}
+    bf = torch.bfloat16
+    k_steps = max(4, args.steps // 2)
+
+    # ---- 12-block FFN stack, 768 -> 3072 -> 768, rank 192, 8192 tokens, sequential freezing
+    rank2 = lrd.quantize_rank(int(0.25 * min(D_MODEL, D_FF)), 64)
+    stack = Stack(lrd, torch, np, si, factorize, rank2, seed_stream=0, true_svd=False)
+    masks = (lrd.freeze_mask(lrd.KIND_SVD, 0), lrd.freeze_mask(lrd.KIND_SVD, 1))
+    ms2 = graph_or_eager(torch, lambda parity: stack.step(masks[parity]), k_steps, 2, graph_ok)
+    fl2 = (stack.flops(masks[0]) + stack.flops(masks[1])) / 2
+    roof2 = 0.0
+    for mask in masks:
+        for b in range(N_BLOCKS):
+            for n_in, n_out, ao, ai, dx in ((D_MODEL, D_FF, True, False, b > 0), (D_FF, D_MODEL, False, True, True)):
+                f, bw = layer_flops(T_TOKENS, n_in, n_out, rank2, mask, want_dx=dx)
+                byf, byb = linear_bytes(T_TOKENS, n_in, n_out, rank2, mask, want_dx=dx, act_out=ao, act_in=ai)
+                roof2 += roof_us(f + bw, byf + byb)[0] / 2
+    del stack
+    torch.cuda.empty_cache()
+    res["ffn_stack_rank192"] = dict(workload="config 2: 12 x (768->3072, GELU, 3072->768), rank 192, 8192 tokens, sequential freezing",
+                                    ms_per_step=ms2, tflops=fl2 / (ms2 * 1e-3) / 1e12, tokens_per_s=T_TOKENS / (ms2 * 1e-3),
+                                    binding_roof_frac=roof2 * 1e-3 / ms2)
+
+    # ---- one 4096 x 4096 layer, 16384 tokens: ranks 256 / 257 / 512 / 1024, first factor frozen, and the dense layer
+    T, d = 16384, 4096
+    gen = torch.Generator(device="cuda").manual_seed(230903824 + 3)
+
+    def rnd(*shape, scale=1.0):
+        return (torch.randn(*shape, device="cuda", generator=gen) * scale).to(bf)
+
+    X, dY = rnd(T, d), rnd(T, d)
+    Y, dX = torch.empty(T, d, dtype=bf, device="cuda"), torch.empty(T, d, dtype=bf, device="cuda")
+    sweep = []
+    for r in (256, 257, 512, 1024):
+        V, U = rnd(r, d, scale=d ** -0.5), rnd(d, r, scale=r ** -0.5)
+        H = torch.empty(T, r, dtype=bf, device="cuda")
+        dV, dU = torch.empty(r, d, device="cuda"), torch.empty(d, r, device="cuda")
+        ws = torch.empty(lrd.linear_workspace_bytes(T, d, d, r, lrd.BF16, 0) + 256, dtype=torch.uint8, device="cuda")
+        fwd = event_us(torch, lambda: lrd.linear_fwd(X, V, U, None, Y, H, ws), 10)
+        bwd = event_us(torch, lambda: lrd.linear_bwd(dY, X, H, V, U, dX, dV, dU, None, 1, ws), 10)
+        f, b = layer_flops(T, d, d, r, 1)
+        byf, byb = linear_bytes(T, d, d, r, 1)
+        t_roof, bound = roof_us(f + b, byf + byb)
+        sweep.append(dict(r=r, fwd_us=fwd, bwd_us_first_factor_frozen=bwd, tflops=(f + b) / ((fwd + bwd) * 1e-6) / 1e12,
+                          frac_bf16_mfma_peak=(f + b) / ((fwd + bwd) * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                          binding_roof=bound, binding_roof_frac=t_roof / (fwd + bwd)))
+        del V, U, H, dV, dU, ws
+    W, dW = rnd(d, d, scale=d ** -0.5), torch.empty(d, d, device="cuda")
+    wsd = torch.empty(lrd.dense_linear_workspace_bytes(T, d, d, lrd.BF16) + 256, dtype=torch.uint8, device="cuda")
+    dense_f = event_us(torch, lambda: lrd.dense_linear_fwd(X, W, None, Y, wsd), 5)
+    dense_b = event_us(torch, lambda: lrd.dense_linear_bwd(dY, X, W, dX, dW, wsd), 5)
+    dense_tf = 6.0 * T * d * d / ((dense_f + dense_b) * 1e-6) / 1e12
+    res["rank_sweep_4096"] = dict(workload="config 3: one 4096 x 4096 linear, 16384 tokens, fwd + bwd with the first factor frozen",
+                                  ranks=sweep, dense=dict(fwd_us=dense_f, bwd_us=dense_b, tflops=dense_tf,
+                                                          frac_bf16_mfma_peak=dense_tf / MFMA_BF16_PEAK_TFLOPS))
+    del X, dY, Y, dX, W, dW, wsd
+    torch.cuda.empty_cache()
+
+    # ---- Tucker-2 3x3 stages, N = 128, ranks C/2, core frozen, and the dense layer
+    stages = []
+    N, k = 128, 3
+    for C, hw in ((64, 56), (128, 28), (256, 14), (512, 7)):
+        r = C // 2
+        P = N * hw * hw
+        g = lrd.conv_geom(N, hw, hw, C, C, r, r, k, 1, 1)
+        Xc, dYc = rnd(N, hw, hw, C), rnd(N, hw, hw, C)
+        Yc, dXc = torch.empty_like(Xc), torch.empty_like(Xc)
+        P1, G, P2 = rnd(r, C, scale=C ** -0.5), rnd(r, k, k, r, scale=(k * k * r) ** -0.5), rnd(C, r, scale=r ** -0.5)
+        A, B = torch.empty(N, hw, hw, r, dtype=bf, device="cuda"), torch.empty(N, hw, hw, r, dtype=bf, device="cuda")
+        dP1, dG, dP2 = torch.empty(r, C, device="cuda"), torch.empty(r, k, k, r, device="cuda"), torch.empty(C, r, device="cuda")
+        ws = torch.empty(lrd.tucker_conv_workspace_bytes(g, lrd.BF16, 0) + 256, dtype=torch.uint8, device="cuda")
+        fwd = event_us(torch, lambda: lrd.tucker_conv_fwd(Xc, P1, G, P2, Yc, A, B, g, ws), 10)
+        bwd = event_us(torch, lambda: lrd.tucker_conv_bwd(dYc, Xc, A, B, P1, G, P2, dXc, dP1, dG, dP2, 0b010, g, ws), 10)
+        f_fwd = 2.0 * P * (C * r + k * k * r * r + r * C)
+        f_bwd = 2.0 * f_fwd - 2.0 * P * k * k * r * r
+        # algorithmic bytes, core frozen: X, Y, dY, dX once each; A, B written and read back; factors; fp32 1x1 gradients
+        byts = 2.0 * (4 * P * C + 4 * P * r) + 2.0 * (2 * C * r + k * k * r * r) + 4.0 * 2 * C * r
+        t_roof, bound = roof_us(f_fwd + f_bwd, byts)
+        Wc, dWc = rnd(C, k, k, C, scale=(k * k * C) ** -0.5), torch.empty(C, k, k, C, device="cuda")
+        wsd = torch.empty(lrd.dense_conv_workspace_bytes(g, lrd.BF16) + 256, dtype=torch.uint8, device="cuda")
+        dfw = event_us(torch, lambda: lrd.dense_conv_fwd(Xc, Wc, Yc, g, wsd), 5)
+        dbw = event_us(torch, lambda: lrd.dense_conv_bwd(dYc, Xc, Wc, dXc, dWc, g, wsd), 5)
+        stages.append(dict(C=C, hw=hw, r=r, fwd_us=fwd, bwd_us_core_frozen=bwd, tflops=(f_fwd + f_bwd) / ((fwd + bwd) * 1e-6) / 1e12,
+                           binding_roof=bound, binding_roof_frac=t_roof / (fwd + bwd), dense_fwd_us=dfw, dense_bwd_us=dbw,
+                           speedup_vs_dense=(dfw + dbw) / (fwd + bwd)))
+    res["tucker_stages"] = dict(workload="config 4: Tucker-2 3x3 stages, NHWC, N = 128, ranks C/2, fwd + bwd with the core frozen", stages=stages)
+    return res
 
 
 if __name__ == "__main__":

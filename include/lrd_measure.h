@@ -2,13 +2,13 @@
  * lrd_measure.h -- measurement aids of the library for low-rank-decomposed layers (see lrd.h).
  *
  * NOT part of the layer ABI.  Nothing here computes any step of the paper's method; these calls
- * exist so that a benchmark can (a) time one product kernel of a layer pass with events on the
+ * exist so that a benchmark can (a) time the product kernels of a layer pass with events on the
  * launch stream, (b) compare the two evaluation orders of a pair (Section 2, Fig. 1: two
  * consecutive layers, with the rank-r intermediate in memory or kept on chip), and (c) measure,
  * in the same run, what the machine delivers to a loop of matrix instructions with no memory in
  * it and to a plain streaming kernel, as denominators next to the published peaks.
  *
- * Unlike the calls of lrd.h, lrd_set_fusion and lrd_profile_next keep PROCESS-WIDE mutable state
+ * Unlike the calls of lrd.h, lrd_set_fusion and the event log keep PROCESS-WIDE mutable state
  * and are not safe against concurrent use from several threads.
  */
 #ifndef LRD_MEASURE_H
@@ -35,13 +35,17 @@ enum { LRD_FUSION_AUTO = 0, LRD_FUSION_ALWAYS = 1, LRD_FUSION_NEVER = 2 };
 int32_t lrd_set_fusion(int32_t mode);
 
 /*
- * Arms a one-shot probe: the next matrix-product kernel the library launches in the given role is
- * bracketed by hipEventRecord(start) / hipEventRecord(stop) on the launch stream (both are
- * caller-owned hipEvent_t passed as void*).  The probe disarms itself after that launch; role 0
- * disarms.  With the fused pair kernel active, the DOWN roles bracket the fused kernel.
+ * Event log of the matrix products of the layer passes.  Between lrd_profile_log_start and
+ * lrd_profile_log_stop every product the library launches (H = X.V^T, dU = dY^T.H, a convolution
+ * core, ...) is bracketed by hipEventRecord on its launch stream with the next pair of caller-owned
+ * events, events[2i] before and events[2i + 1] after product i (hipEvent_t passed as void*), and
+ * described by record i; products beyond n_pairs are not logged.  A product whose reduction is
+ * split (splits > 1) is bracketed together with the kernel that sums its slices.  The caller
+ * synchronises and reads the elapsed times itself.  Logging costs two event records per product,
+ * so it belongs in a separate, eager pass, not in a captured graph.
  */
 enum {
-    LRD_ROLE_NONE = 0,
+    LRD_ROLE_NONE = 0,        /* any other product (convolution layers, dense layers, recomputed intermediates) */
     LRD_ROLE_FWD_DOWN = 1,    /* H  = X.V^T   */
     LRD_ROLE_FWD_UP = 2,      /* Y  = H.U^T   */
     LRD_ROLE_DGRAD_UP = 3,    /* dH = dY.U    */
@@ -49,7 +53,18 @@ enum {
     LRD_ROLE_WGRAD_U = 5,     /* dU = dY^T.H  */
     LRD_ROLE_WGRAD_V = 6      /* dV = dH^T.X  */
 };
-lrd_status lrd_profile_next(int32_t role, void* start_event, void* stop_event);
+typedef struct {
+    int32_t role;             /* LRD_ROLE_* */
+    int32_t gather;           /* 0 plain product, 1 / 2 / 3 convolution forward / data gradient / weight gradient */
+    int32_t epilogue;         /* 0 none, 1 activation stored beside the result, 2 result times activation gradient */
+    int32_t splits;           /* slices of the reduction (1: one kernel) */
+    int64_t M, N, K;          /* result M x N, reduction length K */
+    char kernel[64];          /* the kernel that ran the product (template and tile), NUL-terminated */
+} lrd_profile_record;
+lrd_status lrd_profile_log_start(void** events, int32_t n_pairs);
+/* Stops logging and copies up to `capacity` records to `out` (host, nullable); returns the number of
+ * products logged since lrd_profile_log_start. */
+int32_t lrd_profile_log_stop(lrd_profile_record* out, int32_t capacity);
 
 /*
  * Launches `workgroups` workgroups of four wavefronts that each issue `iters` rounds of four

@@ -36,7 +36,7 @@ EXPORTS = (
     "lrd_gelu_fwd", "lrd_gelu_bwd",
 )
 # measurement aids (include/lrd_measure.h): not part of the layer ABI
-MEASURE_EXPORTS = ("lrd_set_fusion", "lrd_profile_next", "lrd_measure_mfma_loop", "lrd_measure_stream")
+MEASURE_EXPORTS = ("lrd_set_fusion", "lrd_profile_log_start", "lrd_profile_log_stop", "lrd_measure_mfma_loop", "lrd_measure_stream")
 STREAM_READ, STREAM_WRITE, STREAM_COPY = 0, 1, 2
 
 
@@ -48,6 +48,11 @@ class LrdError(RuntimeError):
 
 class Sgd(Structure):
     _fields_ = [("lr", ctypes.c_float), ("momentum", ctypes.c_float), ("weight_decay", ctypes.c_float)]
+
+
+class ProfileRecord(Structure):
+    _fields_ = [("role", c_int32), ("gather", c_int32), ("epilogue", c_int32), ("splits", c_int32),
+                ("M", c_int64), ("N", c_int64), ("K", c_int64), ("kernel", ctypes.c_char * 64)]
 
 
 class ConvGeom(Structure):
@@ -131,8 +136,10 @@ def _load() -> ctypes.CDLL:
     lib.lrd_dense_conv_bwd.argtypes = [P] * 5 + [G, ctypes.c_int, P, SZ, P]
     lib.lrd_gelu_fwd.restype = ctypes.c_int
     lib.lrd_gelu_fwd.argtypes = [P, P, I64, ctypes.c_int, P]
-    lib.lrd_profile_next.restype = ctypes.c_int
-    lib.lrd_profile_next.argtypes = [c_int32, P, P]
+    lib.lrd_profile_log_start.restype = ctypes.c_int
+    lib.lrd_profile_log_start.argtypes = [POINTER(c_void_p), c_int32]
+    lib.lrd_profile_log_stop.restype = c_int32
+    lib.lrd_profile_log_stop.argtypes = [POINTER(ProfileRecord), c_int32]
     lib.lrd_set_fusion.restype = c_int32
     lib.lrd_set_fusion.argtypes = [c_int32]
     lib.lrd_gelu_bwd.restype = ctypes.c_int
@@ -300,9 +307,35 @@ def measure_stream(src, dst, nbytes: int, mode: int, stream=None):
     _check(_lib.lrd_measure_stream(_ptr(src), _ptr(dst), nbytes, mode, _stream(stream)), "lrd_measure_stream")
 
 
-def profile_next(role: int, start: HipEvent = None, stop: HipEvent = None):
-    _check(_lib.lrd_profile_next(role, start.handle if start else None, stop.handle if stop else None),
-           "lrd_profile_next")
+class ProfileLog:
+    """Event log of the library's products (lrd_profile_log_start / _stop): `with ProfileLog(n) as log:`
+    runs eager launches; afterwards log.rows() gives one dict per product with its elapsed microseconds."""
+
+    def __init__(self, n_pairs: int):
+        self.n = int(n_pairs)
+        self.events = [HipEvent() for _ in range(2 * self.n)]          # created ahead of the logged region
+        self.array = (c_void_p * (2 * self.n))(*[e.handle for e in self.events])
+        self.count = 0
+        self.records = None
+
+    def __enter__(self):
+        _check(_lib.lrd_profile_log_start(self.array, self.n), "lrd_profile_log_start")
+        return self
+
+    def __exit__(self, *exc):
+        buf = (ProfileRecord * self.n)()
+        self.count = int(_lib.lrd_profile_log_stop(buf, self.n))
+        self.records = buf
+        return False
+
+    def rows(self):
+        """Call after the device has finished the logged work."""
+        out = []
+        for i in range(min(self.count, self.n)):
+            r = self.records[i]
+            out.append(dict(role=r.role, gather=r.gather, epilogue=r.epilogue, splits=r.splits, M=r.M, N=r.N, K=r.K,
+                            kernel=r.kernel.decode(), us=self.events[2 * i].elapsed_us(self.events[2 * i + 1])))
+        return out
 
 
 # ------------------------------------------------------------------------------- linear pair

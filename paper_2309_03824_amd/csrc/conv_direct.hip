@@ -454,6 +454,7 @@ bool conv_direct_supported(const MatOp& op)
 
 hipError_t conv_direct(const MatOp& op, hipStream_t st)
 {
+    note_kernel("conv3x3_direct (patch staging)");
     const ConvShape& cs = op.cs;
     const bf16_t* A = (const bf16_t*)op.A;
     const bf16_t* B = (const bf16_t*)op.B;

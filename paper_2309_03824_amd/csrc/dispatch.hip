@@ -1,7 +1,11 @@
 // Engine selection for a single matrix product and the split-K policy.
 #include <atomic>
+#include <cstdio>
+#include <mutex>
+#include <vector>
 
 #include "lrd_internal.hpp"
+#include "lrd_measure.h"
 
 namespace lrd {
 
@@ -42,26 +46,37 @@ int choose_splits_act(int64_t M, int64_t N, int64_t K, bool in_bf16)
 }
 
 namespace {
-std::atomic<int> g_probe_role{0};
-hipEvent_t g_probe_start = nullptr, g_probe_stop = nullptr;
+std::mutex g_log_mutex;
+std::atomic<bool> g_log_on{false};
+void** g_log_events = nullptr;
+int g_log_pairs = 0;
+std::vector<lrd_profile_record> g_log;
+thread_local const char* t_kernel = "";
 }  // namespace
 
-void probe_arm(int role, hipEvent_t start, hipEvent_t stop)
+void note_kernel(const char* name) { t_kernel = name; }
+
+int log_begin(hipEvent_t* start, hipEvent_t* stop)
 {
-    g_probe_role.store(0);
-    g_probe_start = start;
-    g_probe_stop = stop;
-    g_probe_role.store(role);
+    if (!g_log_on.load(std::memory_order_relaxed)) return -1;
+    std::lock_guard<std::mutex> lock(g_log_mutex);
+    if (!g_log_on.load() || (int)g_log.size() >= g_log_pairs) return -1;
+    const int i = (int)g_log.size();
+    g_log.push_back(lrd_profile_record{});
+    *start = (hipEvent_t)g_log_events[2 * i];
+    *stop = (hipEvent_t)g_log_events[2 * i + 1];
+    t_kernel = "";
+    return i;
 }
 
-bool probe_take(int role, hipEvent_t* start, hipEvent_t* stop)
+void log_end(int index, int role, int gather, int epilogue, int splits, int64_t M, int64_t N, int64_t K)
 {
-    if (role == 0) return false;
-    int expected = role;
-    if (!g_probe_role.compare_exchange_strong(expected, 0)) return false;
-    *start = g_probe_start;
-    *stop = g_probe_stop;
-    return true;
+    std::lock_guard<std::mutex> lock(g_log_mutex);
+    if (index < 0 || index >= (int)g_log.size()) return;
+    lrd_profile_record& r = g_log[index];
+    r.role = role; r.gather = gather; r.epilogue = epilogue; r.splits = splits;
+    r.M = M; r.N = N; r.K = K;
+    snprintf(r.kernel, sizeof(r.kernel), "%s", t_kernel);
 }
 
 // The activation epilogue as separate elementwise passes, for engines that do not fuse it.
@@ -114,8 +129,8 @@ hipError_t run_matop(const MatOp& op_in, hipStream_t st)
         op.partial = nullptr;
     }
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
-    const bool probed = probe_take(op.role, &ev0, &ev1);
-    if (probed) (void)hipEventRecord(ev0, st);
+    const int logged = log_begin(&ev0, &ev1);
+    if (logged >= 0) (void)hipEventRecord(ev0, st);
     hipError_t e;
     bool epilogue_done = true;
     MatOp flipped;
@@ -137,9 +152,38 @@ hipError_t run_matop(const MatOp& op_in, hipStream_t st)
                           op.sgd->mu, op.sgd->wd, st);
         op.sgd->done = true;
     }
-    if (probed) (void)hipEventRecord(ev1, st);
+    if (logged >= 0) {
+        (void)hipEventRecord(ev1, st);
+        log_end(logged, op.role, op.gather, op.epilogue, op.splits > 1 && op.partial ? op.splits : 1, op.M, op.N, op.K);
+    }
     if (e != hipSuccess || epilogue_done) return e;
     return apply_epilogue(op, st);
 }
 
 }  // namespace lrd
+
+extern "C" {
+
+lrd_status lrd_profile_log_start(void** events, int32_t n_pairs)
+{
+    if (!events || n_pairs < 1) return LRD_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(lrd::g_log_mutex);
+    lrd::g_log.clear();
+    lrd::g_log.reserve((size_t)n_pairs);
+    lrd::g_log_events = events;
+    lrd::g_log_pairs = n_pairs;
+    lrd::g_log_on.store(true);
+    return LRD_OK;
+}
+
+int32_t lrd_profile_log_stop(lrd_profile_record* out, int32_t capacity)
+{
+    std::lock_guard<std::mutex> lock(lrd::g_log_mutex);
+    lrd::g_log_on.store(false);
+    const int32_t n = (int32_t)lrd::g_log.size();
+    if (out)
+        for (int32_t i = 0; i < n && i < capacity; ++i) out[i] = lrd::g_log[i];
+    return n;
+}
+
+}  // extern "C"

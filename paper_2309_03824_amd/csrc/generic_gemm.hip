@@ -184,6 +184,7 @@ hipError_t by_gather(const MatOp& op, hipStream_t st)
 
 hipError_t generic_matop(const MatOp& op, hipStream_t st)
 {
+    note_kernel("generic_gemm_kernel (FMA tiles)");
     if (op.M <= 0 || op.N <= 0) return hipSuccess;
     // Split-K output goes through fp32 partials, so it is only offered for fp32 results.
     if (op.splits > 1 && !op.out_f32) return hipErrorInvalidValue;

@@ -26,10 +26,14 @@ inline bool want_fusion(const ChainOp& ch)
 hipError_t run_chain(const ChainOp& ch, hipStream_t st)
 {
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
-    const bool probed = probe_take(ch.role, &ev0, &ev1);
-    if (probed) (void)hipEventRecord(ev0, st);
+    const int logged = log_begin(&ev0, &ev1);
+    if (logged >= 0) (void)hipEventRecord(ev0, st);
+    note_kernel("chain_kernel (pair through LDS)");
     hipError_t e = mfma_chain(ch, st);
-    if (probed) (void)hipEventRecord(ev1, st);
+    if (logged >= 0) {
+        (void)hipEventRecord(ev1, st);
+        log_end(logged, ch.role, 0, 0, 1, ch.M, ch.N2, ch.K1);
+    }
     return e;
 }
 
@@ -186,14 +190,6 @@ int32_t lrd_set_fusion(int32_t mode)
 {
     if (mode != LRD_FUSION_AUTO && mode != LRD_FUSION_ALWAYS && mode != LRD_FUSION_NEVER) return -1;
     return g_fusion.exchange(mode);
-}
-
-lrd_status lrd_profile_next(int32_t role, void* start_event, void* stop_event)
-{
-    if (role < LRD_ROLE_NONE || role > LRD_ROLE_WGRAD_V) return LRD_ERR_INVALID_ARG;
-    if (role != LRD_ROLE_NONE && (!start_event || !stop_event)) return LRD_ERR_INVALID_ARG;
-    probe_arm(role, (hipEvent_t)start_event, (hipEvent_t)stop_event);
-    return LRD_OK;
 }
 
 // ------------------------------------------------------------------------------------ linear

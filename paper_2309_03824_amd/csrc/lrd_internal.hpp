@@ -95,9 +95,12 @@ struct ChainOp {
 bool mfma_chain_supported(const ChainOp& op);
 hipError_t mfma_chain(const ChainOp& op, hipStream_t st);
 
-// One-shot event probe (lrd_profile_next): returns true and hands out the events if armed for role.
-void probe_arm(int role, hipEvent_t start, hipEvent_t stop);
-bool probe_take(int role, hipEvent_t* start, hipEvent_t* stop);
+// Event log of the products (lrd_profile_log_start / _stop).  log_begin hands out the events of the
+// next record, or returns a negative index when logging is off or the events have run out; log_end
+// fills the record.  note_kernel is called by a launcher with the name of the kernel it launched.
+int log_begin(hipEvent_t* start, hipEvent_t* stop);
+void log_end(int index, int role, int gather, int epilogue, int splits, int64_t M, int64_t N, int64_t K);
+void note_kernel(const char* name);
 
 // Elementwise / reductions.
 hipError_t gelu_fwd(const void* Z, void* A, int64_t n, bool bf16, hipStream_t st);

@@ -502,6 +502,7 @@ bool mfma_matop_supported(const MatOp& op)
 
 hipError_t mfma_matop(const MatOp& op, hipStream_t st)
 {
+    note_kernel("gemm_kernel (any-alignment MFMA)");
     Src A, B;
     bool akm, bkm;
     if (!make_src(op.A, op.a_sm, op.a_sk, op.M, op.K, A, akm)) return hipErrorInvalidValue;

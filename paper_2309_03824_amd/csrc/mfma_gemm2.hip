@@ -19,6 +19,8 @@
 // product per parity class of the input pixel (class = blockIdx.z), each over the taps that reach
 // its pixels, and writes its rows through a row map.
 #include <algorithm>
+#include <cstdio>
+#include <string>
 
 #include "lrd_internal.hpp"
 
@@ -689,6 +691,13 @@ hipError_t launch(const MatOp& op, const Operand& A, const Operand& B, hipStream
         if (e != hipSuccess) return e;
         lds_allowed = true;
     }
+    static const std::string tag = [] {
+        char b[64];
+        snprintf(b, sizeof(b), "gemm2_kernel<%d,%d,%d,%d,%s,%s,%s%s>", BM, BN, WGM, WGN, A_KM ? "A_KM" : "A_KC", B_KM ? "B_KM" : "B_KC",
+                 sizeof(OutT) == 2 ? "bf16" : "f32", G == GATHER_NONE ? "" : ",conv");
+        return std::string(b);
+    }();
+    note_kernel(tag.c_str());
     int kps;
     const int splits = effective_splits(op, &kps);
     float* partial = splits > 1 ? op.partial : nullptr;
