@@ -70,7 +70,8 @@ def test_rank_search_on_measured_times():
     assert R == 77 and R % 8 != 0 and R_min < 64 < R       # a misaligned estimate with aligned ranks inside the range
     ranks = list(range(R_min, R + 1))
     times, t_dense = _measure_curve(2048, n_in, n_out, ranks)
-    noise = 0.03 * sorted(times)[len(times) // 2]
+    # differences below a tenth of the median step are taken as jitter (aligned ranks are ~40 % faster here)
+    noise = 0.1 * sorted(times)[len(times) // 2]
     picks = {}
     for mode in (lrd.SELECT_FIRST_PEAK, lrd.SELECT_ARGMAX, lrd.SELECT_FIRST_PEAK | lrd.SELECT_REQUIRE_FASTER,
                  lrd.SELECT_ARGMAX | lrd.SELECT_REQUIRE_FASTER):
