@@ -168,6 +168,29 @@ lrd_status lrd_linear_bwd(const void* dY, const void* X, const void* H, const vo
                           lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * lrd_linear_bwd for callers that cannot allocate or hand over device memory: code running under
+ * HIP graph capture, tight serving / training loops, harnesses that forbid hipMalloc.  Same
+ * arguments and results as lrd_linear_bwd (bit-identical: the same kernels run), but the scratch
+ * the pass needs (dH, a recomputed H, split-K partial sums) lives in a fixed device array inside
+ * the library instead of a caller workspace.
+ *   - The array holds LRD_STATIC_SCRATCH_BYTES (64 MiB) on every GPU the library is used on, from
+ *     the first call on that GPU until the process ends.
+ *   - A shape whose lrd_linear_workspace_bytes exceeds that size is rejected with
+ *     LRD_ERR_WORKSPACE before anything is launched (lrd_linear_bwd_static_fits tells in advance).
+ *   - The call allocates nothing and frees nothing; the first call on a device looks up the
+ *     array's address (no allocation either).
+ *   - All calls on one GPU share the array and it keeps the previous call's contents; every region
+ *     a pass reads is written by that pass first, so nothing needs clearing.  Two such calls that
+ *     overlap in time on the same GPU (different streams or threads) race; order them.
+ */
+#define LRD_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+int32_t lrd_linear_bwd_static_fits(int64_t T, int64_t in, int64_t out, int64_t r, lrd_dtype dt, uint32_t freeze_mask);
+lrd_status lrd_linear_bwd_static(const void* dY, const void* X, const void* H, const void* V,
+                                 const void* U, void* dX, float* dV, float* dU, float* dbias,
+                                 uint32_t freeze_mask, int64_t T, int64_t in, int64_t out, int64_t r,
+                                 lrd_dtype dt, void* hip_stream);
+
+/*
  * Optimizer of the paper's experiments (Section 3: SGD, momentum 0.9, weight decay 1e-4), in the
  * usual form g' = g + weight_decay * w;  m <- momentum * m + g';  w <- w - lr * m  (a momentum buffer
  * that starts at zero gives the customary first step m = g').

@@ -30,6 +30,7 @@ EXPORTS = (
     "lrd_linear_group_workspace_bytes", "lrd_linear_group_fwd", "lrd_linear_group_bwd",
     "lrd_svd_factors_workspace_bytes", "lrd_svd_factors", "lrd_tucker2_factors_workspace_bytes", "lrd_tucker2_factors",
     "lrd_linear_workspace_bytes", "lrd_linear_fwd", "lrd_linear_bwd", "lrd_linear_fwd_act", "lrd_linear_bwd_act",
+    "lrd_linear_bwd_static", "lrd_linear_bwd_static_fits",
     "lrd_dense_linear_workspace_bytes", "lrd_dense_linear_fwd", "lrd_dense_linear_bwd",
     "lrd_tucker_conv_workspace_bytes", "lrd_tucker_conv_fwd", "lrd_tucker_conv_bwd",
     "lrd_dense_conv_workspace_bytes", "lrd_dense_conv_fwd", "lrd_dense_conv_bwd",
@@ -100,6 +101,10 @@ def _load() -> ctypes.CDLL:
     lib.lrd_linear_fwd.argtypes = [P] * 6 + [I64] * 4 + [ctypes.c_int, P, SZ, P]
     lib.lrd_linear_bwd.restype = ctypes.c_int
     lib.lrd_linear_bwd.argtypes = [P] * 9 + [U32] + [I64] * 4 + [ctypes.c_int, P, SZ, P]
+    lib.lrd_linear_bwd_static.restype = ctypes.c_int
+    lib.lrd_linear_bwd_static.argtypes = [P] * 9 + [U32] + [I64] * 4 + [ctypes.c_int, P]
+    lib.lrd_linear_bwd_static_fits.restype = c_int32
+    lib.lrd_linear_bwd_static_fits.argtypes = [I64] * 4 + [ctypes.c_int, U32]
     lib.lrd_sgd_step.restype = ctypes.c_int
     lib.lrd_sgd_step.argtypes = [P, P, P, P, ctypes.c_int, I64, ctypes.POINTER(Sgd), P]
     lib.lrd_linear_sgd_workspace_bytes.restype = SZ
@@ -361,6 +366,23 @@ def linear_bwd(dY, X, H, V, U, dX, dV, dU, dbias, freeze_mask, ws=None, stream=N
     _check(_lib.lrd_linear_bwd(_ptr(dY), _ptr(X), _ptr(H), _ptr(V), _ptr(U), _ptr(dX), _ptr(dV), _ptr(dU),
                                _ptr(dbias), freeze_mask, T, n_in, n_out, r, _dt(dY), wp, wb, _stream(stream)),
            "lrd_linear_bwd")
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def linear_bwd_static_fits(T, n_in, n_out, r, dtype, freeze_mask=0) -> bool:
+    return bool(_lib.lrd_linear_bwd_static_fits(T, n_in, n_out, r, dtype, freeze_mask))
+
+
+def linear_bwd_static(dY, X, H, V, U, dX, dV, dU, dbias, freeze_mask, stream=None):
+    """lrd_linear_bwd on the library's own fixed scratch array (no workspace argument, no allocation)."""
+    T, n_out = dY.shape
+    r, n_in = V.shape
+    assert U.shape == (n_out, r)
+    _check(_lib.lrd_linear_bwd_static(_ptr(dY), _ptr(X), _ptr(H), _ptr(V), _ptr(U), _ptr(dX), _ptr(dV), _ptr(dU),
+                                      _ptr(dbias), freeze_mask, T, n_in, n_out, r, _dt(dY), _stream(stream)),
+           "lrd_linear_bwd_static")
 
 
 def sgd_step(w_master, momentum_buf, grad, w_copy, opt: "Sgd", stream=None):

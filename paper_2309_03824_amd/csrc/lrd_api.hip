@@ -2,6 +2,7 @@
 // pass out of matrix products (see lrd.h for the contract of every call).
 #include <algorithm>
 #include <atomic>
+#include <mutex>
 
 #include "lrd.h"
 #include "lrd_internal.hpp"
@@ -413,6 +414,50 @@ lrd_status lrd_linear_bwd_act(const void* dY, const void* X, const void* H, cons
 {
     return linear_bwd_impl(dY, X, H, V, U, dX, dV, dU, dbias, freeze_mask, Z_in, act, T, in, out, r, dt, ws, ws_bytes, hip_stream,
                            nullptr, nullptr);
+}
+
+// ------------------------------------------------------------------------------------ allocation-free backward
+namespace {
+// Scratch of lrd_linear_bwd_static.  In host code this name is only a handle for the symbol, not a
+// device address: the address on each GPU comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char scratch[LRD_STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+std::mutex g_scratch_mutex;
+
+// Address of `scratch` on the current device, or nullptr if the runtime refuses.
+void* scratch_on_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+int32_t lrd_linear_bwd_static_fits(int64_t T, int64_t in, int64_t out, int64_t r, lrd_dtype dt, uint32_t freeze_mask)
+{
+    const size_t need = lrd_linear_workspace_bytes(T, in, out, r, dt, freeze_mask);
+    if (!dtype_ok(dt) || !linear_dims_ok(T, in, out, r)) return 0;
+    return need <= LRD_STATIC_SCRATCH_BYTES ? 1 : 0;
+}
+
+lrd_status lrd_linear_bwd_static(const void* dY, const void* X, const void* H, const void* V, const void* U, void* dX,
+                                 float* dV, float* dU, float* dbias, uint32_t freeze_mask, int64_t T, int64_t in,
+                                 int64_t out, int64_t r, lrd_dtype dt, void* hip_stream)
+{
+    if (!dtype_ok(dt) || !linear_dims_ok(T, in, out, r)) return LRD_ERR_INVALID_ARG;
+    if (!lrd_linear_bwd_static_fits(T, in, out, r, dt, freeze_mask)) return LRD_ERR_WORKSPACE;
+    void* ws = scratch_on_current_device();
+    if (!ws) return LRD_ERR_RUNTIME;
+    return lrd_linear_bwd(dY, X, H, V, U, dX, dV, dU, dbias, freeze_mask, T, in, out, r, dt, ws, LRD_STATIC_SCRATCH_BYTES,
+                          hip_stream);
 }
 
 // ------------------------------------------------------------------------------------ optimizer
