@@ -123,6 +123,22 @@ bool conv_dgrad_as_fwd(const MatOp& op, MatOp* fwd)
 
 hipError_t run_matop(const MatOp& op_in, hipStream_t st)
 {
+    if (op_in.batch > 1 && !mfma_gemm2_supported(op_in)) {
+        // no engine takes this batch in one launch: one product at a time
+        const int64_t ein = op_in.in_bf16 ? 2 : 4, eout = op_in.out_f32 ? 4 : ein;
+        for (int b = 0; b < op_in.batch; ++b) {
+            MatOp one = op_in;
+            one.batch = 1;
+            one.A = (const char*)op_in.A + b * op_in.a_bs * ein;
+            one.B = (const char*)op_in.B + b * op_in.b_bs * ein;
+            one.C = (char*)op_in.C + b * op_in.c_bs * eout;
+            if (op_in.bias) one.bias = op_in.bias + b * op_in.bias_bs;
+            if (op_in.aux) one.aux = (char*)op_in.aux + b * op_in.aux_bs * ein;
+            hipError_t e = run_matop(one, st);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
     MatOp op = op_in;
     if (!op.out_f32 && op.splits > 1 && !mfma_gemm2_supported(op)) {
         op.splits = 1;   // the other engines split K only towards fp32 results

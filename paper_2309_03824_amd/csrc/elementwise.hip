@@ -14,12 +14,12 @@ __global__ __launch_bounds__(256) void gelu_fwd_bf16(const bf16_t* __restrict__ 
         bf16x8 z = *reinterpret_cast<const bf16x8*>(Z + g * 8);
         bf16x8 a;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) a[e] = (bf16_t)gelu_f((float)z[e]);
+        for (int e = 0; e < 8; ++e) a[e] = (bf16_t)gelu_bf16_f((float)z[e]);
         *reinterpret_cast<bf16x8*>(A + g * 8) = a;
     }
     if (blockIdx.x == 0 && threadIdx.x < n - n8 * 8) {
         int64_t i = n8 * 8 + threadIdx.x;
-        A[i] = (bf16_t)gelu_f((float)Z[i]);
+        A[i] = (bf16_t)gelu_bf16_f((float)Z[i]);
     }
 }
 
@@ -33,12 +33,12 @@ __global__ __launch_bounds__(256) void gelu_bwd_bf16(const bf16_t* dA, const bf1
         bf16x8 d = *reinterpret_cast<const bf16x8*>(dA + g * 8);
         bf16x8 o;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = (bf16_t)((float)d[e] * gelu_grad_f((float)z[e]));
+        for (int e = 0; e < 8; ++e) o[e] = (bf16_t)((float)d[e] * gelu_grad_bf16_f((float)z[e]));
         *reinterpret_cast<bf16x8*>(dZ + g * 8) = o;
     }
     if (blockIdx.x == 0 && threadIdx.x < n - n8 * 8) {
         int64_t i = n8 * 8 + threadIdx.x;
-        dZ[i] = (bf16_t)((float)dA[i] * gelu_grad_f((float)Z[i]));
+        dZ[i] = (bf16_t)((float)dA[i] * gelu_grad_bf16_f((float)Z[i]));
     }
 }
 

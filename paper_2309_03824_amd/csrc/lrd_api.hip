@@ -534,8 +534,9 @@ size_t group_partial_region(int64_t T, int64_t in, int64_t out, int64_t r, int32
 {
     const size_t h = act_partial_bytes(T, G * r, in, dt);
     if (!backward) return h;
+    // the groups' second-factor gradients are one batched product: G sets of slices side by side
     return std::max(std::max(h, act_partial_bytes(T, r, out, dt)),
-                    std::max(partial_bytes(out, r, T, dt), partial_bytes(G * r, in, T, dt)));
+                    std::max((size_t)G * partial_bytes(out, r, T, dt), partial_bytes(G * r, in, T, dt)));
 }
 }  // namespace
 
@@ -569,13 +570,13 @@ lrd_status lrd_linear_group_fwd(const void* X, const void* V_cat, const void* U,
     g1.role = LRD_ROLE_FWD_DOWN;
     share_splits(g1, region, dt, SPLIT_ACT);
     LRD_TRY(run_matop(g1, st));
-    for (int32_t g = 0; g < groups; ++g) {
-        MatOp g2 = nt(at(H, g * r, dt), gr, at(U, (int64_t)g * out * r, dt), r, (void*)at(Y, (int64_t)g * T * out, dt), out, T, out, r,
-                      dt, false);
-        g2.bias = bias ? bias + (int64_t)g * out : nullptr;
-        g2.role = LRD_ROLE_FWD_UP;
-        LRD_TRY(run_matop(g2, st));
-    }
+    // the groups' second products, one launch: group g reads columns g*r.. of H and its own U, writes its own Y
+    MatOp g2 = nt(H, gr, U, r, Y, out, T, out, r, dt, false);
+    g2.bias = bias;
+    g2.role = LRD_ROLE_FWD_UP;
+    g2.batch = groups;
+    g2.a_bs = r; g2.b_bs = out * r; g2.c_bs = T * out; g2.bias_bs = out;
+    LRD_TRY(run_matop(g2, st));
     return LRD_OK;
 }
 
@@ -603,11 +604,20 @@ lrd_status lrd_linear_group_bwd(const void* dY, const void* X, const void* H, co
     if (!cv.ok) return LRD_ERR_WORKSPACE;
 
     if (need_dH) {
-        for (int32_t g = 0; g < groups; ++g) {
-            MatOp d1 = nn(at(dY, (int64_t)g * T * out, dt), out, at(U, (int64_t)g * out * r, dt), r, (void*)at(dH, g * r, dt), gr, T,
-                          r, out, dt);
+        if (choose_splits_act(T, r, out, dt == LRD_BF16) > 1) {
+            // few tokens: each group's product is sliced along K and summed into its columns of dH
+            for (int32_t g = 0; g < groups; ++g) {
+                MatOp d1 = nn(at(dY, (int64_t)g * T * out, dt), out, at(U, (int64_t)g * out * r, dt), r, (void*)at(dH, g * r, dt), gr,
+                              T, r, out, dt);
+                d1.role = LRD_ROLE_DGRAD_UP;
+                share_splits(d1, region, dt, SPLIT_ACT);
+                LRD_TRY(run_matop(d1, st));
+            }
+        } else {
+            MatOp d1 = nn(dY, out, U, r, dH, gr, T, r, out, dt);
             d1.role = LRD_ROLE_DGRAD_UP;
-            share_splits(d1, region, dt, SPLIT_ACT);
+            d1.batch = groups;
+            d1.a_bs = T * out; d1.b_bs = out * r; d1.c_bs = r;
             LRD_TRY(run_matop(d1, st));
         }
         if (dX) {
@@ -624,12 +634,13 @@ lrd_status lrd_linear_group_bwd(const void* dY, const void* X, const void* H, co
             LRD_TRY(run_matop(re, st));
             Hs = Hre;
         }
-        for (int32_t g = 0; g < groups; ++g) {
-            MatOp wu = tn(at(dY, (int64_t)g * T * out, dt), out, at(Hs, g * r, dt), gr, dU + (int64_t)g * out * r, r, out, r, T, dt);
-            wu.role = LRD_ROLE_WGRAD_U;
-            share_splits(wu, region, dt, SPLIT_WGRAD);
-            LRD_TRY(run_matop(wu, st));
-        }
+        // one launch for the groups' gradients: group g contracts its dY with its columns of H
+        MatOp wu = tn(dY, out, Hs, gr, dU, r, out, r, T, dt);
+        wu.role = LRD_ROLE_WGRAD_U;
+        wu.batch = groups;
+        wu.a_bs = T * out; wu.b_bs = r; wu.c_bs = out * r;
+        share_splits(wu, region, dt, SPLIT_WGRAD);
+        LRD_TRY(run_matop(wu, st));
     }
     if (train_v) {
         MatOp wv = tn(dH, gr, X, in, dV_cat, in, gr, in, T, dt);

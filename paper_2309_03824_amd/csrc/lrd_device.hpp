@@ -64,6 +64,41 @@ __device__ __forceinline__ float gelu_grad_f(float z)
     return fmaf(z, phi, Phi);
 }
 
+// The same two functions for results that are rounded to bf16 (8 bits of mantissa): odd polynomials in
+// the clamped argument, Phi(z) ~ 1/2 + c Q6(c^2) with c = clamp(z, +-4) (|error| <= 1.2e-4) and
+// gelu'(z) ~ 1/2 + c R8(c^2) with c = clamp(z, +-4.5) (|error| <= 2.6e-4), least-squares fits on
+// Chebyshev nodes.  No exponential and no reciprocal: 10-12 full-rate instructions per element against
+// ~25 for the form above.  An epilogue that applies the activation to every element of a wide result
+// is bound by exactly this instruction count (the vector unit does not run while the same wave's matrix
+// instructions issue), so it is what the fused epilogues and the bf16 elementwise passes use.
+__device__ __forceinline__ float gelu_bf16_f(float z)
+{
+    const float c = __builtin_amdgcn_fmed3f(z, -4.0f, 4.0f);
+    const float s = c * c;
+    float q = fmaf(2.804369359e-08f, s, -1.888105544e-06f);
+    q = fmaf(q, s, 5.417549619e-05f);
+    q = fmaf(q, s, -8.796401089e-04f);
+    q = fmaf(q, s, 9.121535346e-03f);
+    q = fmaf(q, s, -6.542359293e-02f);
+    q = fmaf(q, s, 3.985679448e-01f);
+    return z * fmaf(c, q, 0.5f);
+}
+
+__device__ __forceinline__ float gelu_grad_bf16_f(float z)
+{
+    const float c = __builtin_amdgcn_fmed3f(z, -4.5f, 4.5f);
+    const float s = c * c;
+    float q = fmaf(4.164355527e-10f, s, -4.259615949e-08f);
+    q = fmaf(q, s, 1.884581820e-06f);
+    q = fmaf(q, s, -4.748817082e-05f);
+    q = fmaf(q, s, 7.562761311e-04f);
+    q = fmaf(q, s, -7.982769981e-03f);
+    q = fmaf(q, s, 5.659934506e-02f);
+    q = fmaf(q, s, -2.627864778e-01f);
+    q = fmaf(q, s, 7.970107198e-01f);
+    return fmaf(c, q, 0.5f);
+}
+
 // MFMA operand fragment (v_mfma_f32_32x32x16_bf16: lane L holds row (L & 31), k = 8 * (L >> 5) + 0..7)
 // out of a k-major LDS tile [k][row] with LDM elements between consecutive k: two transposing reads.
 // Within a block of 16 lanes, ds_read_b64_tr_b16 hands lane l the element (l & 3) of the 8-byte words

@@ -60,6 +60,10 @@ struct MatOp {
     size_t scratch_bytes = 0;
     // Optional optimizer step on the finished fp32 result (a dense weight gradient, ldc == N).
     const SgdFuse* sgd = nullptr;
+    // A batch of products of one shape (the layers of a group): product z reads A + z * a_bs,
+    // B + z * b_bs, bias + z * bias_bs and writes C + z * c_bs, aux + z * aux_bs (element strides).
+    int batch = 1;
+    int64_t a_bs = 0, b_bs = 0, c_bs = 0, aux_bs = 0, bias_bs = 0;
 };
 enum { EPI_NONE = 0, EPI_ACT_STORE = 1, EPI_ACT_GRAD = 2 };
 

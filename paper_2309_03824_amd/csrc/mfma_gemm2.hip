@@ -41,6 +41,12 @@ struct Operand {
     int rows;     // extent along the tile's row index (M for A, N for B)
 };
 
+// A batch of products of one shape in one launch (element strides between consecutive products).
+struct BatchArgs {
+    int batch = 1, nsplit = 1;
+    int64_t a_bs = 0, b_bs = 0, c_bs = 0, aux_bs = 0, bias_bs = 0;
+};
+
 // Plain (strided) operands are read with buffer loads: the descriptor's base is the tile's first
 // element for this K-step (wave-uniform), each chunk keeps one 32-bit byte offset, and the range
 // check of the descriptor returns zeros for anything past the operand's last element.  A chunk
@@ -520,14 +526,14 @@ __device__ __forceinline__ void store_bf16_tile(const f32x16 (&acc)[TM][TN], bf1
         if (epilogue == EPI_ACT_GRAD) {
             bf16x8 c8 = __builtin_bit_cast(bf16x8, v);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) c8[e] = (bf16_t)((float)c8[e] * gelu_grad_f((float)z8[q][e]));
+            for (int e = 0; e < 8; ++e) c8[e] = (bf16_t)((float)c8[e] * gelu_grad_bf16_f((float)z8[q][e]));
             v = __builtin_bit_cast(u32x4, c8);
         }
         if (ok) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + mrow * ldc + n));
         if (epilogue == EPI_ACT_STORE) {
             bf16x8 c8 = __builtin_bit_cast(bf16x8, v);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) c8[e] = (bf16_t)gelu_f((float)c8[e]);
+            for (int e = 0; e < 8; ++e) c8[e] = (bf16_t)gelu_bf16_f((float)c8[e]);
             if (ok) __builtin_nontemporal_store(__builtin_bit_cast(u32x4, c8), reinterpret_cast<u32x4*>(aux + (int64_t)m * ldaux + n));
         }
     }
@@ -537,7 +543,7 @@ template <int BM, int BN, int WGM, int WGN, int DEPTH, bool A_KM, bool B_KM, cla
 __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm2_kernel(Operand A, Operand B, ConvShape cs, OutT* __restrict__ C, int64_t ldc,
                                                                const float* __restrict__ bias, float* __restrict__ partial,
                                                                int M, int N, int K, int k_per_split, int epilogue,
-                                                               bf16_t* __restrict__ aux, int64_t ldaux)
+                                                               bf16_t* __restrict__ aux, int64_t ldaux, BatchArgs bt)
 {
     constexpr int NT = 64 * WGM * WGN;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
@@ -549,7 +555,20 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm2_kernel(Operand A, Ope
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
     const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
-    int kbeg = blockIdx.z * k_per_split;
+    // blockIdx.z = K-slice, or (batch index, K-slice) for a batch of products of one shape
+    int zslice = blockIdx.z, zbatch = 0;
+    if constexpr (G == GATHER_NONE) {
+        if (bt.batch > 1) {
+            zbatch = blockIdx.z / bt.nsplit;
+            zslice = blockIdx.z - zbatch * bt.nsplit;
+            A.p += zbatch * bt.a_bs;
+            B.p += zbatch * bt.b_bs;
+            C += zbatch * bt.c_bs;
+            if (bias) bias += zbatch * bt.bias_bs;
+            if (aux) aux += zbatch * bt.aux_bs;
+        }
+    }
+    int kbeg = zslice * k_per_split;
     if constexpr (G == GATHER_CONV_DGRAD) {
         if (cs.cls) {
             // all parity classes of a strided data gradient in one launch: blockIdx.z is the class,
@@ -647,7 +666,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm2_kernel(Operand A, Ope
     const int r = lane & 31, h = lane >> 5;
     if constexpr (sizeof(OutT) == 4) {
         // fp32 results (weight gradients or their split-K partials): 16-byte stores straight from registers
-        float* out = partial ? partial + (int64_t)blockIdx.z * M * N : reinterpret_cast<float*>(C);
+        // slices of a batch lie [slice][batch][M][N], so that the sum over slices sees one tall matrix
+        float* out = partial ? partial + ((int64_t)zslice * bt.batch + zbatch) * M * N : reinterpret_cast<float*>(C);
         const int64_t ldo = partial ? (int64_t)N : ldc;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -702,13 +722,19 @@ hipError_t launch(const MatOp& op, const Operand& A, const Operand& B, hipStream
     const int splits = effective_splits(op, &kps);
     float* partial = splits > 1 ? op.partial : nullptr;
     if (sizeof(OutT) == 4 && !op.out_f32 && !partial) return hipErrorInvalidValue;   // fp32 tiles need the reduce to reach a bf16 C
-    dim3 grid((unsigned)ceil_div(op.M, BM), (unsigned)ceil_div(op.N, BN), (unsigned)splits);
+    BatchArgs bt;
+    bt.batch = G == GATHER_NONE ? op.batch : 1;
+    bt.nsplit = splits;
+    bt.a_bs = op.a_bs; bt.b_bs = op.b_bs; bt.c_bs = op.c_bs; bt.aux_bs = op.aux_bs; bt.bias_bs = op.bias_bs;
+    dim3 grid((unsigned)ceil_div(op.M, BM), (unsigned)ceil_div(op.N, BN), (unsigned)(splits * bt.batch));
     if (G == GATHER_CONV_DGRAD && op.cs.cls) grid.z = (unsigned)(op.cs.stride * op.cs.stride);   // one slab of workgroups per parity class
     hipLaunchKernelGGL(kern, grid, dim3(NT), lds_bytes, st, A, B, op.cs, (OutT*)op.C, op.ldc, op.bias, partial, (int)op.M,
-                       (int)op.N, (int)op.K, kps, op.epilogue, (bf16_t*)op.aux, op.ldaux);
+                       (int)op.N, (int)op.K, kps, op.epilogue, (bf16_t*)op.aux, op.ldaux, bt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (splits > 1) return reduce_partials(op.partial, op.C, !op.out_f32, op.ldc, op.M, op.N, splits, st, op.out_f32 ? op.sgd : nullptr);
+    // a batch of sliced products is summed as one matrix of batch * M rows (supported() admits only dense results)
+    if (splits > 1)
+        return reduce_partials(op.partial, op.C, !op.out_f32, op.ldc, op.M * bt.batch, op.N, splits, st, op.out_f32 ? op.sgd : nullptr);
     return hipSuccess;
 }
 
@@ -719,7 +745,7 @@ template <bool A_KM, bool B_KM, class OutT, int G = GATHER_NONE>
 hipError_t by_tile(const MatOp& op, const Operand& A, const Operand& B, hipStream_t st)
 {
     const int64_t splits = effective_splits(op, nullptr);
-    auto wgs = [&](int bm, int bn) { return ceil_div(op.M, bm) * ceil_div(op.N, bn) * splits; };
+    auto wgs = [&](int bm, int bn) { return ceil_div(op.M, bm) * ceil_div(op.N, bn) * splits * (G == GATHER_NONE ? op.batch : 1); };
     if constexpr (sizeof(OutT) == 2 && !A_KM && !B_KM && G == GATHER_NONE) {
         if (op.K >= 1024 && wgs(256, 256) >= 224) return launch<256, 256, 2, 4, 2, false, false, OutT>(op, A, B, st);
     }
@@ -786,6 +812,13 @@ bool mfma_gemm2_supported(const MatOp& op)
         if (op.bias && (op.N < 4 || (reinterpret_cast<uintptr_t>(op.bias) & 15u))) return false;
     }
     if (ceil_div(op.N, 64) > 65535) return false;
+    if (op.batch < 1 || op.batch > 1024) return false;
+    if (op.batch > 1) {
+        if (op.gather != GATHER_NONE || op.sgd) return false;
+        if (op.a_bs % 8 != 0 || op.b_bs % 8 != 0 || op.c_bs % 8 != 0 || op.aux_bs % 8 != 0 || op.bias_bs % 4 != 0) return false;
+        // sliced reductions of a batch are summed as one tall dense matrix
+        if (op.splits > 1 && op.partial && (!op.out_f32 || op.ldc != op.N || op.c_bs != op.M * op.N)) return false;
+    }
     if (op.gather == GATHER_NONE && ((akm ? op.a_sk : op.a_sm) > BUF_MAX_LD || (bkm ? op.b_sk : op.b_sn) > BUF_MAX_LD)) return false;
     if (op.epilogue != EPI_NONE && (op.out_f32 || !op.aux || !al16(op.aux) || op.ldaux % 8 != 0)) return false;
     return true;
