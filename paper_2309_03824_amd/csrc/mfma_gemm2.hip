@@ -746,8 +746,12 @@ hipError_t by_tile(const MatOp& op, const Operand& A, const Operand& B, hipStrea
 {
     const int64_t splits = effective_splits(op, nullptr);
     auto wgs = [&](int bm, int bn) { return ceil_div(op.M, bm) * ceil_div(op.N, bn) * splits * (G == GATHER_NONE ? op.batch : 1); };
-    if constexpr (sizeof(OutT) == 2 && !A_KM && !B_KM && G == GATHER_NONE) {
-        if (op.K >= 1024 && wgs(256, 256) >= 224) return launch<256, 256, 2, 4, 2, false, false, OutT>(op, A, B, st);
+    // Large products in every layout: 256 x 256 tiles on eight waves (wave tile 128 x 64: 0.75 KB of LDS
+    // fragment reads per matrix instruction against 1 KB for a 64 x 64 wave tile; LDS reads are what
+    // bounds these kernels).  16384 x 4096 x 4096: forward 551 -> 445 us, data gradient 609 -> 440 us,
+    // weight gradient 538 -> 407 us against 128 x 128 tiles.
+    if constexpr (G == GATHER_NONE && ((sizeof(OutT) == 2 && !A_KM) || (sizeof(OutT) == 4 && A_KM && B_KM))) {
+        if (op.K >= 1024 && wgs(256, 256) >= 224) return launch<256, 256, 2, 4, 2, A_KM, B_KM, OutT>(op, A, B, st);
     }
     // Results at most 32 columns wide (1x1 and core convolutions at Tucker ranks <= 32): a 128 x 32 tile
     // does a quarter of the MFMA and LDS work of a 128 x 128 one (15 against 23 us at 401408 x 32 x 64).
