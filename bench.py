@@ -842,6 +842,18 @@ def factorize_bench(args, torch, np, si, lrd):
         err = float(torch.linalg.norm(Wd.double() - rec) / torch.linalg.norm(Wd.double()))
         rows.append(dict(kind="tucker2", S=S, C=C, k=k, r1=r1, r2=r1, gpu_ms=ms, sweeps=sweeps,
                          host_lapack_fp64_ms=host_ms, rel_error=err))
+    # the 24 weights of the FFN stack (12 x 3072x768 and 12 x 768x3072) as two batched calls, against 24 single calls
+    for n_out, n_in, r in ((3072, 768, 192), (768, 3072, 192)):
+        B = 12
+        rng = si.rng_for(6, 9000 + n_out)
+        Wb = torch.from_numpy(np.stack([si.linear_weight(n_out, n_in, rng).astype(np.float32) for _ in range(B)])).cuda()
+        U = torch.empty((B, n_out, r), dtype=torch.float32, device="cuda")
+        V = torch.empty((B, r, n_in), dtype=torch.float32, device="cuda")
+        wsb = torch.empty(lrd.svd_factors_batched_workspace_bytes(B, n_out, n_in) + 256, dtype=torch.uint8, device="cuda")
+        ms_b, (_, sweeps) = clock(lambda: lrd.svd_factors_batched(Wb, r, U, V, wsb))
+        ws1 = torch.empty(lrd.svd_factors_workspace_bytes(n_out, n_in) + 256, dtype=torch.uint8, device="cuda")
+        ms_1, _ = clock(lambda: [lrd.svd_factors(Wb[b], r, U[b], V[b], ws1) for b in range(B)])
+        rows.append(dict(kind="svd batch of 12", out=n_out, **{"in": n_in}, r=r, batched_ms=ms_b, twelve_single_calls_ms=ms_1, sweeps=sweeps))
     print(json.dumps(dict(metric="one-time factorization on the device (fp64 one-sided Jacobi), milliseconds", cases=rows)))
 
 
@@ -942,6 +954,14 @@ def measure_peaks(torch, lrd):
             fl[0] = lrd.measure_mfma_loop(sink, wgs, 2048)
         us = event_us(torch, run, 3)
         res[f"mfma_bf16_loop_tflops_{wgs}_workgroups"] = fl[0] / (us * 1e-6) / 1e12
+    # LDS fragment reads: two workgroups per compute unit on all 256 units
+    isink = sink.view(torch.int32)
+    lb = [0.0]
+
+    def run_lds():
+        lb[0] = lrd.measure_lds_read(isink, 512, 4000)
+    us = event_us(torch, run_lds, 3)
+    res["lds_read_16B_fragments_bytes_per_ns_per_cu"] = lb[0] / 256 / (us * 1e3)
     n = 1 << 30
     a = torch.empty(n, dtype=torch.uint8, device="cuda")
     b = torch.empty(n, dtype=torch.uint8, device="cuda")

@@ -350,6 +350,18 @@ size_t lrd_svd_factors_workspace_bytes(int64_t out, int64_t in);
 lrd_status lrd_svd_factors(const float* W, int64_t out, int64_t in, int64_t r, float* U, float* V,
                            double* sigma_host, int32_t* sweeps_host, void* ws, size_t ws_bytes, void* hip_stream);
 
+/*
+ * The same factorization for a batch of weights of one shape (the layers of a stack), W [batch][out x in],
+ * U [batch][out x r], V [batch][r x in], all dense and consecutive; sigma_host [batch][min(out,in)] or NULL;
+ * *sweeps_host = the largest number of sweeps any part of the batch took.  Every tournament step of the
+ * Jacobi iteration (eq. 1) is one launch over all matrices of a group and the convergence test is read
+ * once per sweep for the group; groups are sized so that their working set stays in the last-level cache.
+ * Each matrix gets the factors lrd_svd_factors would give it (same rotations, same order).
+ */
+size_t lrd_svd_factors_batched_workspace_bytes(int64_t batch, int64_t out, int64_t in);
+lrd_status lrd_svd_factors_batched(const float* W, int64_t batch, int64_t out, int64_t in, int64_t r, float* U, float* V,
+                                   double* sigma_host, int32_t* sweeps_host, void* ws, size_t ws_bytes, void* hip_stream);
+
 /* Workspace bytes of lrd_tucker2_factors for a weight [S][k][k][C] (0 on bad sizes). */
 size_t lrd_tucker2_factors_workspace_bytes(int64_t S, int64_t C, int32_t k);
 

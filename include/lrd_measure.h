@@ -76,6 +76,15 @@ int32_t lrd_profile_log_stop(lrd_profile_record* out, int32_t capacity);
 lrd_status lrd_measure_mfma_loop(float* sink, int32_t workgroups, int32_t iters, double* flops_host, void* hip_stream);
 
 /*
+ * Launches `workgroups` workgroups of four wavefronts that each read `iters` rounds of eight 16-byte
+ * words per lane from LDS, in the conflict-free pattern of an operand fragment; the caller times the
+ * launch.  *bytes_host (host, nullable) receives the LDS bytes read by the launch (divide by the time
+ * and by the compute units the workgroups cover for bytes per second per unit).  sink: device, at least
+ * workgroups * 256 words.  Stateless.
+ */
+lrd_status lrd_measure_lds_read(uint32_t* sink, int32_t workgroups, int32_t iters, double* bytes_host, void* hip_stream);
+
+/*
  * One pass of a plain streaming kernel over `bytes` bytes (a multiple of 16; 16 bytes per lane
  * per access): LRD_STREAM_READ sums src into a few words of dst (dst: at least 16 KiB),
  * LRD_STREAM_WRITE fills dst, LRD_STREAM_COPY copies src to dst.  src / dst are device pointers,

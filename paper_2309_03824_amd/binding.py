@@ -28,7 +28,7 @@ EXPORTS = (
     "lrd_status_string", "lrd_quantize_rank", "lrd_freeze_mask", "lrd_tucker_rank", "lrd_svd_rank", "lrd_select_rank",
     "lrd_sgd_step", "lrd_linear_sgd_workspace_bytes", "lrd_linear_bwd_sgd",
     "lrd_linear_group_workspace_bytes", "lrd_linear_group_fwd", "lrd_linear_group_bwd",
-    "lrd_svd_factors_workspace_bytes", "lrd_svd_factors", "lrd_tucker2_factors_workspace_bytes", "lrd_tucker2_factors",
+    "lrd_svd_factors_workspace_bytes", "lrd_svd_factors", "lrd_svd_factors_batched_workspace_bytes", "lrd_svd_factors_batched", "lrd_tucker2_factors_workspace_bytes", "lrd_tucker2_factors",
     "lrd_linear_workspace_bytes", "lrd_linear_fwd", "lrd_linear_bwd", "lrd_linear_fwd_act", "lrd_linear_bwd_act",
     "lrd_linear_bwd_static", "lrd_linear_bwd_static_fits",
     "lrd_dense_linear_workspace_bytes", "lrd_dense_linear_fwd", "lrd_dense_linear_bwd",
@@ -37,7 +37,7 @@ EXPORTS = (
     "lrd_gelu_fwd", "lrd_gelu_bwd",
 )
 # measurement aids (include/lrd_measure.h): not part of the layer ABI
-MEASURE_EXPORTS = ("lrd_set_fusion", "lrd_profile_log_start", "lrd_profile_log_stop", "lrd_measure_mfma_loop", "lrd_measure_stream")
+MEASURE_EXPORTS = ("lrd_set_fusion", "lrd_profile_log_start", "lrd_profile_log_stop", "lrd_measure_mfma_loop", "lrd_measure_lds_read", "lrd_measure_stream")
 STREAM_READ, STREAM_WRITE, STREAM_COPY = 0, 1, 2
 
 
@@ -88,6 +88,11 @@ def _load() -> ctypes.CDLL:
     lib.lrd_svd_factors.restype = c_int32
     lib.lrd_svd_factors.argtypes = [c_void_p, I64, I64, I64, c_void_p, c_void_p, ctypes.POINTER(c_double),
                                     ctypes.POINTER(c_int32), c_void_p, c_size_t, c_void_p]
+    lib.lrd_svd_factors_batched_workspace_bytes.restype = c_size_t
+    lib.lrd_svd_factors_batched_workspace_bytes.argtypes = [I64, I64, I64]
+    lib.lrd_svd_factors_batched.restype = c_int32
+    lib.lrd_svd_factors_batched.argtypes = [c_void_p, I64, I64, I64, I64, c_void_p, c_void_p, ctypes.POINTER(c_double),
+                                            ctypes.POINTER(c_int32), c_void_p, c_size_t, c_void_p]
     lib.lrd_tucker2_factors_workspace_bytes.restype = c_size_t
     lib.lrd_tucker2_factors_workspace_bytes.argtypes = [I64, I64, c_int32]
     lib.lrd_tucker2_factors.restype = c_int32
@@ -151,6 +156,8 @@ def _load() -> ctypes.CDLL:
     lib.lrd_gelu_bwd.argtypes = [P, P, P, I64, ctypes.c_int, P]
     lib.lrd_measure_mfma_loop.restype = ctypes.c_int
     lib.lrd_measure_mfma_loop.argtypes = [P, c_int32, c_int32, POINTER(c_double), P]
+    lib.lrd_measure_lds_read.restype = ctypes.c_int
+    lib.lrd_measure_lds_read.argtypes = [P, c_int32, c_int32, POINTER(c_double), P]
     lib.lrd_measure_stream.restype = ctypes.c_int
     lib.lrd_measure_stream.argtypes = [P, P, SZ, c_int32, P]
     return lib
@@ -238,6 +245,24 @@ def svd_factors(W, r: int, U, V, ws, stream=None):
     return list(sig), int(sweeps.value)
 
 
+def svd_factors_batched_workspace_bytes(batch: int, n_out: int, n_in: int) -> int:
+    return int(_lib.lrd_svd_factors_batched_workspace_bytes(batch, n_out, n_in))
+
+
+def svd_factors_batched(W, r: int, U, V, ws, stream=None):
+    """Device SVD pairs of a batch W [B, out, in] (fp32); returns (singular values [B][min] as lists, max sweeps)."""
+    B, n_out, n_in = W.shape
+    assert U.shape == (B, n_out, r) and V.shape == (B, r, n_in)
+    k = min(n_out, n_in)
+    sig = (c_double * (B * k))()
+    sweeps = c_int32(0)
+    wp, wb = _ws(ws)
+    _check(_lib.lrd_svd_factors_batched(_ptr(W), B, n_out, n_in, r, _ptr(U), _ptr(V), sig, ctypes.byref(sweeps), wp, wb,
+                                        _stream(stream)), "lrd_svd_factors_batched")
+    flat = list(sig)
+    return [flat[b * k:(b + 1) * k] for b in range(B)], int(sweeps.value)
+
+
 def tucker2_factors_workspace_bytes(S: int, C: int, k: int) -> int:
     return int(_lib.lrd_tucker2_factors_workspace_bytes(S, C, k))
 
@@ -306,6 +331,14 @@ def measure_mfma_loop(sink, workgroups: int, iters: int, stream=None) -> float:
     fl = c_double(0.0)
     _check(_lib.lrd_measure_mfma_loop(_ptr(sink), workgroups, iters, ctypes.byref(fl), _stream(stream)), "lrd_measure_mfma_loop")
     return float(fl.value)
+
+
+def measure_lds_read(sink, workgroups: int, iters: int, stream=None) -> float:
+    """Launches the LDS read loop; returns the LDS bytes read by the launch."""
+    assert sink.numel() >= workgroups * 256
+    nb = c_double(0.0)
+    _check(_lib.lrd_measure_lds_read(_ptr(sink), workgroups, iters, ctypes.byref(nb), _stream(stream)), "lrd_measure_lds_read")
+    return float(nb.value)
 
 
 def measure_stream(src, dst, nbytes: int, mode: int, stream=None):

@@ -27,9 +27,14 @@ constexpr int MAX_SWEEPS = 60;
 inline size_t round256(size_t b) { return (b + 255) & ~size_t(255); }
 
 // M[i][j] = transpose ? W[j][i] : W[i][j]  (W row-major with leading dimension ldw), Q = identity.
+// Every kernel of the Jacobi iteration takes a batch of problems of one shape: blockIdx.y selects the
+// matrix, consecutive matrices lie bw / bm / bq elements apart (W, M, Q).
+struct BatchStride { int64_t bw = 0, bm = 0, bq = 0; };
+
 __global__ __launch_bounds__(FT) void load_matrix_kernel(const float* __restrict__ W, int64_t ldw, bool transpose,
-                                                         double* __restrict__ M, double* __restrict__ Q, int p, int q)
+                                                         double* __restrict__ M, double* __restrict__ Q, int p, int q, BatchStride bs)
 {
+    W += blockIdx.y * bs.bw; M += blockIdx.y * bs.bm; Q += blockIdx.y * bs.bq;
     const int64_t total = (int64_t)p * q, stride = (int64_t)gridDim.x * FT;
     for (int64_t e = (int64_t)blockIdx.x * FT + threadIdx.x; e < total; e += stride) {
         int i = (int)(e / q), j = (int)(e - (int64_t)i * q);
@@ -61,8 +66,9 @@ __device__ __forceinline__ double block_sum(double v, double* scratch)
 // rotate): workgroup k pairs (n - 1, step) for k = 0 and ((step + k) mod (n - 1), (step - k) mod (n - 1))
 // otherwise.  Players >= p are byes.
 __global__ __launch_bounds__(FT) void jacobi_step_kernel(double* __restrict__ M, double* __restrict__ Q, int p, int q, int n,
-                                                         int step, double tol, unsigned int* __restrict__ rotations)
+                                                         int step, double tol, unsigned int* __restrict__ rotations, BatchStride bs)
 {
+    M += blockIdx.y * bs.bm; Q += blockIdx.y * bs.bq;
     __shared__ double scratch[FT];
     __shared__ double cs[2];
     const int k = blockIdx.x, m = n - 1;
@@ -116,9 +122,10 @@ __global__ __launch_bounds__(FT) void jacobi_step_kernel(double* __restrict__ M,
 }
 
 // sigma[i] = |row i of M|
-__global__ __launch_bounds__(FT) void row_norms_kernel(const double* __restrict__ M, int q, double* __restrict__ sigma)
+__global__ __launch_bounds__(FT) void row_norms_kernel(const double* __restrict__ M, int q, double* __restrict__ sigma, BatchStride bs)
 {
     __shared__ double scratch[FT];
+    M += blockIdx.y * bs.bm; sigma += (int64_t)blockIdx.y * gridDim.x;
     const double* r = M + (int64_t)blockIdx.x * q;
     double s = 0.0;
     for (int j = threadIdx.x; j < q; j += FT) s += r[j] * r[j];
@@ -131,8 +138,11 @@ __global__ __launch_bounds__(FT) void row_norms_kernel(const double* __restrict_
 // Otherwise (M = W^T) the roles of the two row spaces swap.
 __global__ __launch_bounds__(FT) void emit_pair_kernel(const double* __restrict__ M, const double* __restrict__ Q,
                                                        const double* __restrict__ sigma, const int* __restrict__ order, int p,
-                                                       int q, int r, bool wide, float* __restrict__ U, float* __restrict__ V)
+                                                       int q, int r, bool wide, float* __restrict__ U, float* __restrict__ V,
+                                                       BatchStride bs, int64_t ustride, int64_t vstride)
 {
+    M += blockIdx.y * bs.bm; Q += blockIdx.y * bs.bq; sigma += (int64_t)blockIdx.y * p; order += (int64_t)blockIdx.y * p;
+    U += blockIdx.y * ustride; V += blockIdx.y * vstride;
     const int j = blockIdx.x, row = order[j];
     const double sg = sigma[row];
     const double down = sg > 0.0 ? 1.0 / sqrt(sg) : 0.0, up = sqrt(sg);
@@ -227,25 +237,36 @@ struct JacobiBuffers {
     unsigned int* rotations;
 };
 
-size_t jacobi_bytes(int64_t p, int64_t q)
+size_t jacobi_bytes(int64_t p, int64_t q, int64_t batch = 1)
 {
-    return round256((size_t)p * q * 8) + round256((size_t)p * p * 8) + round256((size_t)p * 8) + round256((size_t)p * 4) + 256;
+    return round256((size_t)batch * p * q * 8) + round256((size_t)batch * p * p * 8) + round256((size_t)batch * p * 8) +
+           round256((size_t)batch * p * 4) + 256;
 }
 
-JacobiBuffers carve_jacobi(char*& at, int64_t p, int64_t q)
+JacobiBuffers carve_jacobi(char*& at, int64_t p, int64_t q, int64_t batch = 1)
 {
     JacobiBuffers jb;
-    jb.M = (double*)at;            at += round256((size_t)p * q * 8);
-    jb.Q = (double*)at;            at += round256((size_t)p * p * 8);
-    jb.sigma = (double*)at;        at += round256((size_t)p * 8);
-    jb.order = (int*)at;           at += round256((size_t)p * 4);
+    jb.M = (double*)at;            at += round256((size_t)batch * p * q * 8);
+    jb.Q = (double*)at;            at += round256((size_t)batch * p * p * 8);
+    jb.sigma = (double*)at;        at += round256((size_t)batch * p * 8);
+    jb.order = (int*)at;           at += round256((size_t)batch * p * 4);
     jb.rotations = (unsigned int*)at; at += 256;
     return jb;
 }
 
-// Sweeps until no pair rotates; then singular values to the host, descending order to the device.
+// Matrices of a batch factorized together: as many as keep the iteration's working set (M and Q of
+// every matrix, read and written once per tournament step) inside the last-level cache.
+int64_t jacobi_chunk(int64_t p, int64_t q, int64_t batch)
+{
+    const int64_t per = (p * q + p * p) * 8;
+    return std::max<int64_t>(1, std::min<int64_t>(batch, (int64_t(96) << 20) / std::max<int64_t>(per, 1)));
+}
+
+// Sweeps until no pair rotates (in any matrix of the batch: one counter, one host read per sweep); then
+// singular values to the host, descending order to the device (both [batch][p]).
 // Returns the sweeps used, or -1 on a runtime error, -2 if MAX_SWEEPS did not suffice.
-int run_jacobi(const JacobiBuffers& jb, int p, int q, std::vector<double>& sigma_host, std::vector<int>& order_host, hipStream_t st)
+int run_jacobi(const JacobiBuffers& jb, int p, int q, std::vector<double>& sigma_host, std::vector<int>& order_host, hipStream_t st,
+               int batch = 1, BatchStride bs = BatchStride{})
 {
     const int n = (p + 1) & ~1;       // players of the tournament (one bye when p is odd)
     int sweeps = 0;
@@ -254,7 +275,7 @@ int run_jacobi(const JacobiBuffers& jb, int p, int q, std::vector<double>& sigma
         // the counter is cleared by a kernel-free path the stream orders with the launches
         if (hipMemsetAsync(jb.rotations, 0, sizeof(unsigned int), st) != hipSuccess) return -1;
         for (int step = 0; step < n - 1; ++step)
-            hipLaunchKernelGGL(jacobi_step_kernel, dim3(n / 2), dim3(FT), 0, st, jb.M, jb.Q, p, q, n, step, JACOBI_TOL, jb.rotations);
+            hipLaunchKernelGGL(jacobi_step_kernel, dim3(n / 2, batch), dim3(FT), 0, st, jb.M, jb.Q, p, q, n, step, JACOBI_TOL, jb.rotations, bs);
         if (hipGetLastError() != hipSuccess) return -1;
         unsigned int count = 0;
         if (hipMemcpyAsync(&count, jb.rotations, sizeof count, hipMemcpyDeviceToHost, st) != hipSuccess) return -1;
@@ -263,14 +284,18 @@ int run_jacobi(const JacobiBuffers& jb, int p, int q, std::vector<double>& sigma
         converged = count == 0;
     }
     if (!converged) return -2;
-    hipLaunchKernelGGL(row_norms_kernel, dim3(p), dim3(FT), 0, st, jb.M, q, jb.sigma);
-    sigma_host.resize(p);
-    if (hipMemcpyAsync(sigma_host.data(), jb.sigma, (size_t)p * 8, hipMemcpyDeviceToHost, st) != hipSuccess) return -1;
+    hipLaunchKernelGGL(row_norms_kernel, dim3(p, batch), dim3(FT), 0, st, jb.M, q, jb.sigma, bs);
+    sigma_host.resize((size_t)p * batch);
+    if (hipMemcpyAsync(sigma_host.data(), jb.sigma, (size_t)p * batch * 8, hipMemcpyDeviceToHost, st) != hipSuccess) return -1;
     if (hipStreamSynchronize(st) != hipSuccess) return -1;
-    order_host.resize(p);
-    std::iota(order_host.begin(), order_host.end(), 0);
-    std::stable_sort(order_host.begin(), order_host.end(), [&](int x, int y) { return sigma_host[x] > sigma_host[y]; });
-    if (hipMemcpyAsync(jb.order, order_host.data(), (size_t)p * 4, hipMemcpyHostToDevice, st) != hipSuccess) return -1;
+    order_host.resize((size_t)p * batch);
+    for (int b = 0; b < batch; ++b) {
+        int* ord = order_host.data() + (size_t)b * p;
+        const double* sg = sigma_host.data() + (size_t)b * p;
+        std::iota(ord, ord + p, 0);
+        std::stable_sort(ord, ord + p, [&](int x, int y) { return sg[x] > sg[y]; });
+    }
+    if (hipMemcpyAsync(jb.order, order_host.data(), (size_t)p * batch * 4, hipMemcpyHostToDevice, st) != hipSuccess) return -1;
     if (hipStreamSynchronize(st) != hipSuccess) return -1;     // order_host may be reused by the caller
     return sweeps;
 }
@@ -302,17 +327,62 @@ lrd_status lrd_svd_factors(const float* W, int64_t out, int64_t in, int64_t r, f
     const int p = (int)std::min(out, in), q = (int)std::max(out, in);
     char* at = (char*)ws;
     JacobiBuffers jb = carve_jacobi(at, p, q);
-    hipLaunchKernelGGL(load_matrix_kernel, dim3(blocks_for((int64_t)p * q)), dim3(FT), 0, st, W, in, !wide, jb.M, jb.Q, p, q);
+    hipLaunchKernelGGL(load_matrix_kernel, dim3(blocks_for((int64_t)p * q)), dim3(FT), 0, st, W, in, !wide, jb.M, jb.Q, p, q, BatchStride{});
     if (hipGetLastError() != hipSuccess) return LRD_ERR_RUNTIME;
     std::vector<double> sg;
     std::vector<int> order;
     const int sweeps = run_jacobi(jb, p, q, sg, order, st);
     if (sweeps < 0) return LRD_ERR_RUNTIME;
-    hipLaunchKernelGGL(emit_pair_kernel, dim3((unsigned)r), dim3(FT), 0, st, jb.M, jb.Q, jb.sigma, jb.order, p, q, (int)r, wide, U, V);
+    hipLaunchKernelGGL(emit_pair_kernel, dim3((unsigned)r), dim3(FT), 0, st, jb.M, jb.Q, jb.sigma, jb.order, p, q, (int)r, wide, U, V,
+                       BatchStride{}, (int64_t)0, (int64_t)0);
     if (hipGetLastError() != hipSuccess || hipStreamSynchronize(st) != hipSuccess) return LRD_ERR_RUNTIME;
     if (sigma_host)
         for (int j = 0; j < p; ++j) sigma_host[j] = sg[order[j]];
     if (sweeps_host) *sweeps_host = sweeps;
+    return LRD_OK;
+}
+
+size_t lrd_svd_factors_batched_workspace_bytes(int64_t batch, int64_t out, int64_t in)
+{
+    if (batch < 1 || out < 1 || in < 1 || out >= (int64_t(1) << 20) || in >= (int64_t(1) << 20)) return 0;
+    const int64_t p = std::min(out, in), q = std::max(out, in);
+    return jacobi_bytes(p, q, jacobi_chunk(p, q, batch));
+}
+
+lrd_status lrd_svd_factors_batched(const float* W, int64_t batch, int64_t out, int64_t in, int64_t r, float* U, float* V,
+                                   double* sigma_host, int32_t* sweeps_host, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    if (!W || !U || !V || batch < 1 || batch > 65535 || out < 1 || in < 1 || r < 1 || r > std::min(out, in)) return LRD_ERR_INVALID_ARG;
+    if (out >= (int64_t(1) << 20) || in >= (int64_t(1) << 20)) return LRD_ERR_INVALID_ARG;
+    if (!aligned16(W) || !aligned16(U) || !aligned16(V) || !aligned16(ws)) return LRD_ERR_ALIGNMENT;
+    if (!ws || ws_bytes < lrd_svd_factors_batched_workspace_bytes(batch, out, in)) return LRD_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const bool wide = out <= in;
+    const int p = (int)std::min(out, in), q = (int)std::max(out, in);
+    const int64_t chunk = jacobi_chunk(p, q, batch);
+    std::vector<double> sg;
+    std::vector<int> order;
+    int max_sweeps = 0;
+    for (int64_t b0 = 0; b0 < batch; b0 += chunk) {
+        const int nb = (int)std::min(chunk, batch - b0);
+        char* at = (char*)ws;
+        JacobiBuffers jb = carve_jacobi(at, p, q, chunk);
+        BatchStride bs;
+        bs.bw = out * in; bs.bm = (int64_t)p * q; bs.bq = (int64_t)p * p;
+        hipLaunchKernelGGL(load_matrix_kernel, dim3(blocks_for((int64_t)p * q), nb), dim3(FT), 0, st, W + b0 * out * in, in, !wide, jb.M,
+                           jb.Q, p, q, bs);
+        if (hipGetLastError() != hipSuccess) return LRD_ERR_RUNTIME;
+        const int sweeps = run_jacobi(jb, p, q, sg, order, st, nb, bs);
+        if (sweeps < 0) return LRD_ERR_RUNTIME;
+        max_sweeps = std::max(max_sweeps, sweeps);
+        hipLaunchKernelGGL(emit_pair_kernel, dim3((unsigned)r, nb), dim3(FT), 0, st, jb.M, jb.Q, jb.sigma, jb.order, p, q, (int)r, wide,
+                           U + b0 * out * r, V + b0 * r * in, bs, out * r, r * in);
+        if (hipGetLastError() != hipSuccess || hipStreamSynchronize(st) != hipSuccess) return LRD_ERR_RUNTIME;
+        if (sigma_host)
+            for (int b = 0; b < nb; ++b)
+                for (int j = 0; j < p; ++j) sigma_host[(b0 + b) * p + j] = sg[(size_t)b * p + order[(size_t)b * p + j]];
+    }
+    if (sweeps_host) *sweeps_host = max_sweeps;
     return LRD_OK;
 }
 
@@ -367,7 +437,7 @@ lrd_status lrd_tucker2_factors(const float* W, int64_t S, int64_t C, int32_t k, 
         JacobiBuffers jb = carve_jacobi(j0, ps, qs);
         const bool tall = S > C * kk;
         hipLaunchKernelGGL(load_matrix_kernel, dim3(blocks_for(S * kk * C)), dim3(FT), 0, st, W, kk * C, tall, jb.M, jb.Q, (int)ps,
-                           (int)qs);
+                           (int)qs, BatchStride{});
         if (hipGetLastError() != hipSuccess) return LRD_ERR_RUNTIME;
         int sw = run_jacobi(jb, (int)ps, (int)qs, sg, order, st);
         if (sw < 0) return LRD_ERR_RUNTIME;

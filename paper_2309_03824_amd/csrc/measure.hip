@@ -30,6 +30,27 @@ __global__ __launch_bounds__(256) void mfma_loop_kernel(float* __restrict__ sink
     sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// Every lane reads 16 bytes of LDS per access in the pattern of an operand fragment of the matrix
+// instruction (32 rows, a row pitch that spreads them over the banks: no conflicts), 8 accesses per
+// round; nothing else runs, so the launch time is the LDS read time.
+__global__ __launch_bounds__(256) void lds_read_kernel(unsigned* __restrict__ sink, int iters)
+{
+    extern __shared__ __align__(16) unsigned char lds_bytes[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    for (int i = tid; i < 8192; i += 256) reinterpret_cast<unsigned*>(lds_bytes)[i] = (unsigned)i;
+    __syncthreads();
+    const unsigned char* base = lds_bytes + (lane & 31) * 528 + (lane >> 5) * 16;
+    unsigned acc = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const u32x4 v = *reinterpret_cast<const volatile u32x4*>(base + k * 32);
+            acc += v.x + v.y + v.z + v.w;
+        }
+    }
+    sink[(size_t)blockIdx.x * 256 + tid] = acc;
+}
+
 constexpr int STREAM_THREADS = 256;
 constexpr int STREAM_PER_THREAD = 8;   // 16-byte accesses per thread: 32 KiB per workgroup
 
@@ -78,6 +99,15 @@ lrd_status lrd_measure_mfma_loop(float* sink, int32_t workgroups, int32_t iters,
     if (hipGetLastError() != hipSuccess) return LRD_ERR_RUNTIME;
     // 4 waves x iters x 4 instructions x (32 x 32 x 16 multiply-adds)
     if (flops_host) *flops_host = (double)workgroups * 4.0 * (double)iters * 4.0 * 2.0 * 32.0 * 32.0 * 16.0;
+    return LRD_OK;
+}
+
+lrd_status lrd_measure_lds_read(uint32_t* sink, int32_t workgroups, int32_t iters, double* bytes_host, void* hip_stream)
+{
+    if (!sink || workgroups < 1 || workgroups > (1 << 20) || iters < 1) return LRD_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(lds_read_kernel, dim3((unsigned)workgroups), dim3(256), 32768, (hipStream_t)hip_stream, sink, (int)iters);
+    if (hipGetLastError() != hipSuccess) return LRD_ERR_RUNTIME;
+    if (bytes_host) *bytes_host = (double)workgroups * 256.0 * (double)iters * 8.0 * 16.0;
     return LRD_OK;
 }
 

@@ -101,3 +101,32 @@ def test_tucker2_matches_oracle(geo):
     assert np.max(np.abs(P1.T @ P1 - P1o.T @ P1o)) <= 1e-5                  # the same leading subspaces
     assert np.max(np.abs(P2 @ P2.T - P2o @ P2o.T)) <= 1e-5
     assert np.max(np.abs(_reconstruct(P1, G, P2) - _reconstruct(P1o, Go, P2o))) <= 1e-5 * scale
+
+
+@pytest.mark.parametrize("shape_r_b", [((96, 160), 24, 5), ((200, 64), 16, 3), ((40, 40), 40, 7)])
+def test_batched_svd_pairs_match_oracle_and_single_calls(shape_r_b):
+    """A batch of weights of one shape in one call: every matrix against the oracle, and bit for bit against
+    lrd_svd_factors on the same matrix (the batch applies the same rotations in the same order, the extra
+    sweeps a slower neighbour forces rotate nothing)."""
+    (n_out, n_in), r, B = shape_r_b
+    rng = si.rng_for(6, 5000 + n_out + B)
+    k = min(n_out, n_in)
+    Ws = []
+    for b in range(B):
+        W = si.gaussian((n_out, n_in), rng) * 0.05
+        W += (si.haar_orthogonal(n_out, rng)[:, :k] * np.exp(-np.arange(k) / max(4.0, k / (4.0 + b)))) @ si.haar_orthogonal(n_in, rng)[:k, :]
+        Ws.append(W.astype(np.float32))
+    W32 = np.stack(Ws)
+    U = torch.empty((B, n_out, r), dtype=torch.float32, device="cuda")
+    V = torch.empty((B, r, n_in), dtype=torch.float32, device="cuda")
+    ws = workspace(lrd.svd_factors_batched_workspace_bytes(B, n_out, n_in))
+    sig, sweeps = lrd.svd_factors_batched(_f32(W32), r, U, V, ws)
+    assert 1 <= sweeps <= 30
+    Uh, Vh = host(U), host(V)
+    for b in range(B):
+        Uo, Vo, so = oracle.svd_factors(W32[b].astype(np.float64), r)
+        s = np.array(sig[b])
+        assert np.max(np.abs(s - so)) <= 1e-9 * so[0]
+        assert np.max(np.abs(Uh[b] @ Vh[b] - Uo @ Vo)) <= 2e-6 * so[0]
+        U1, V1, s1, _ = _run_svd(W32[b], r)
+        assert np.array_equal(U1, Uh[b]) and np.array_equal(V1, Vh[b])
