@@ -191,13 +191,18 @@ def roof_us(flops, nbytes):
 
 
 class Encoder:
-    """The decomposed linears of a 12-layer encoder (hidden 1024, FFN 4096), rank r; fwd/bwd through the library only."""
+    """The decomposed linears of a 12-layer encoder (hidden 1024, FFN 4096), rank r; fwd/bwd through the library only.
 
-    def __init__(self, lrd, torch, np, si, rank, seed_stream, layers=ENC_LAYERS, grouped=True):
+    Every per-layer tensor is a slice of a stack over the layers.  deferred=True runs the backward in
+    two parts: data gradients layer by layer, then the weight gradients of all layers of one shape in
+    one call each (the stacks hand that call its operands at a fixed stride)."""
+
+    def __init__(self, lrd, torch, np, si, rank, seed_stream, layers=ENC_LAYERS, grouped=True, deferred=False):
         self.lrd, self.torch, self.r, self.n_layers, self.grouped = lrd, torch, rank, layers, grouped
+        self.deferred = deferred and grouped
         dev, bf = "cuda", torch.bfloat16
         rng = si.rng_for(5, seed_stream)
-        T, d, ff = ENC_T, ENC_D, ENC_FF
+        T, d, ff, L = ENC_T, ENC_D, ENC_FF, layers
 
         def to_dev(a):
             bits = si.bf16_bits(a).view(np.int16)
@@ -206,29 +211,46 @@ class Encoder:
         def empty(*shape, dt=bf):
             return torch.empty(shape, dtype=dt, device=dev)
 
-        def pair(n_out, n_in):
+        def stack(n_out, n_in):
+            return dict(H=empty(L, T, rank), dH=empty(L, T, rank), dU=empty(L, n_out, rank, dt=torch.float32),
+                        dV=empty(L, rank, n_in, dt=torch.float32))
+
+        self.st = dict(o=stack(d, d), up=stack(ff, d), dn=stack(d, ff),
+                       qkv=dict(H=empty(L, T, 3 * rank), dH=empty(L, T, 3 * rank), dU=empty(L, 3, d, rank, dt=torch.float32),
+                                dU_by_member=empty(3, L, d, rank, dt=torch.float32), dV=empty(L, 3 * rank, d, dt=torch.float32)))
+        # stand-ins for what the (unchanged, not run) attention hands to and receives from these layers
+        self.attn, self.dqkv = empty(L, T, d), empty(L, 3, T, d)
+        self.Xo, self.Z, self.A = empty(L, T, d), empty(L, T, ff), empty(L, T, ff)
+        # gradient stacks: G[l] enters layer l's second FFN linear (G[L-1] is the stack's own output)
+        self.G, self.gZ, self.gXo, self.gAttn = empty(L, T, d), empty(L, T, ff), empty(L, T, d), empty(T, d)
+        self.Xs = empty(L, T, d)
+        self.Xs[0].copy_(to_dev(si.gaussian((T, d), rng)))
+        self.X = [self.Xs[l] for l in range(L)] + [self.G[L - 1]]
+
+        def pair(name, l, n_out, n_in):
             U, V = si.direct_factors(n_out, n_in, rank, rng)
-            return dict(U=to_dev(U), V=to_dev(V), H=empty(T, rank), dU=empty(n_out, rank, dt=torch.float32),
-                        dV=empty(rank, n_in, dt=torch.float32))
+            return dict(U=to_dev(U), V=to_dev(V), H=self.st[name]["H"][l], dH=self.st[name]["dH"][l], dU=self.st[name]["dU"][l],
+                        dV=self.st[name]["dV"][l])
 
         self.layers = []
-        for _ in range(layers):
+        for l in range(L):
             qkv = [si.direct_factors(d, d, rank, rng) for _ in range(3)]
-            L = dict(o=pair(d, d), up=pair(ff, d), dn=pair(d, ff),
-                     qkv=dict(U=to_dev(np.stack([u for u, _ in qkv])), V=to_dev(np.concatenate([v for _, v in qkv], axis=0)),
-                              H=empty(T, 3 * rank), dU=empty(3, d, rank, dt=torch.float32), dV=empty(3 * rank, d, dt=torch.float32),
-                              Y=empty(3, T, d), Hs=None if grouped else [empty(T, rank) for _ in range(3)]),
-                     # stand-ins for what the (unchanged, not run) attention hands to and receives from these layers
-                     attn=to_dev(si.gaussian((T, d), rng)), dqkv=to_dev(si.gaussian((3, T, d), rng, 1e-2)),
-                     Xo=empty(T, d), Z=empty(T, ff), A=empty(T, ff))
-            self.layers.append(L)
-        self.X = [to_dev(si.gaussian((T, d), rng))] + [empty(T, d) for _ in range(layers)]
-        self.gX = [empty(T, d) for _ in range(2)]
-        self.gXo, self.gAttn, self.gZ = empty(T, d), empty(T, d), empty(T, ff)
+            q = self.st["qkv"]
+            Lr = dict(o=pair("o", l, d, d), up=pair("up", l, ff, d), dn=pair("dn", l, d, ff),
+                      qkv=dict(U=to_dev(np.stack([u for u, _ in qkv])), V=to_dev(np.concatenate([v for _, v in qkv], axis=0)),
+                               H=q["H"][l], dH=q["dH"][l], dU=q["dU"][l], dV=q["dV"][l],
+                               Y=empty(3, T, d), Hs=None if grouped else [empty(T, rank) for _ in range(3)]),
+                      attn=self.attn[l], dqkv=self.dqkv[l], Xo=self.Xo[l], Z=self.Z[l], A=self.A[l])
+            self.attn[l].copy_(to_dev(si.gaussian((T, d), rng)))
+            self.dqkv[l].copy_(to_dev(si.gaussian((3, T, d), rng, 1e-2)))
+            self.layers.append(Lr)
         self.gQ = None if grouped else [empty(T, d) for _ in range(3)]
         nbytes = max(lrd.linear_workspace_bytes(T, d, d, rank, lrd.BF16, 0), lrd.linear_workspace_bytes(T, d, ff, rank, lrd.BF16, 0),
                      lrd.linear_workspace_bytes(T, ff, d, rank, lrd.BF16, 0),
-                     lrd.linear_group_workspace_bytes(T, d, d, rank, 3, lrd.BF16, 0))
+                     lrd.linear_group_workspace_bytes(T, d, d, rank, 3, lrd.BF16, 0),
+                     lrd.linear_wgrad_batched_workspace_bytes(L, T, d, d, 3 * rank, lrd.BF16, 0),
+                     lrd.linear_wgrad_batched_workspace_bytes(L, T, d, ff, rank, lrd.BF16, 0),
+                     lrd.linear_wgrad_batched_workspace_bytes(L, T, ff, d, rank, lrd.BF16, 0))
         self.ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
 
     def forward(self):
@@ -246,17 +268,18 @@ class Encoder:
 
     def backward(self, mask):
         """Loss 0.5 ||X_last||^2: the gradient entering the last layer is the stack's output."""
+        if self.deferred:
+            return self.backward_deferred(mask)
         lrd = self.lrd
-        g = self.X[self.n_layers]
         for l in reversed(range(self.n_layers)):
             L = self.layers[l]
             q, o, up, dn = L["qkv"], L["o"], L["up"], L["dn"]
-            out = self.gX[l & 1]
-            lrd.linear_bwd_act(g, L["A"], dn["H"], dn["V"], dn["U"], self.gZ, dn["dV"], dn["dU"], None, mask, L["Z"], lrd.ACT_GELU, self.ws)
-            lrd.linear_bwd(self.gZ, L["Xo"], up["H"], up["V"], up["U"], self.gXo, up["dV"], up["dU"], None, mask, self.ws)
-            lrd.linear_bwd(self.gXo, L["attn"], o["H"], o["V"], o["U"], self.gAttn, o["dV"], o["dU"], None, mask, self.ws)
+            g, out = self.G[l], (self.G[l - 1] if l > 0 else None)
+            lrd.linear_bwd_act(g, L["A"], dn["H"], dn["V"], dn["U"], self.gZ[l], dn["dV"], dn["dU"], None, mask, L["Z"], lrd.ACT_GELU, self.ws)
+            lrd.linear_bwd(self.gZ[l], L["Xo"], up["H"], up["V"], up["U"], self.gXo[l], up["dV"], up["dU"], None, mask, self.ws)
+            lrd.linear_bwd(self.gXo[l], L["attn"], o["H"], o["V"], o["U"], self.gAttn, o["dV"], o["dU"], None, mask, self.ws)
             if self.grouped:
-                lrd.linear_group_bwd(L["dqkv"], self.X[l], q["H"], q["V"], q["U"], out if l > 0 else None, q["dV"], q["dU"], None, mask, self.ws)
+                lrd.linear_group_bwd(L["dqkv"], self.X[l], q["H"], q["V"], q["U"], out, q["dV"], q["dU"], None, mask, self.ws)
             else:
                 # three separate layers; their input gradients are added afterwards (glue, not the library's)
                 for i in range(3):
@@ -265,7 +288,28 @@ class Encoder:
                 if l > 0:
                     self.torch.add(self.gQ[0], self.gQ[1], out=out)
                     out.add_(self.gQ[2])
-            g = out
+
+    def backward_deferred(self, mask):
+        lrd, r, st = self.lrd, self.r, self.st
+        for l in reversed(range(self.n_layers)):
+            L = self.layers[l]
+            q, o, up, dn = L["qkv"], L["o"], L["up"], L["dn"]
+            lrd.linear_bwd_data(self.G[l], dn["V"], dn["U"], self.gZ[l], dn["dH"], L["Z"], lrd.ACT_GELU, self.ws)
+            lrd.linear_bwd_data(self.gZ[l], up["V"], up["U"], self.gXo[l], up["dH"], None, lrd.ACT_NONE, self.ws)
+            lrd.linear_bwd_data(self.gXo[l], o["V"], o["U"], self.gAttn, o["dH"], None, lrd.ACT_NONE, self.ws)
+            lrd.linear_group_bwd_data(L["dqkv"], q["V"], q["U"], self.G[l - 1] if l > 0 else None, q["dH"], self.ws)
+        tu, tv = not mask & 2, not mask & 1
+        for name, dY, X in (("dn", self.G, self.A), ("up", self.gZ, self.Xo), ("o", self.gXo, self.attn)):
+            s = st[name]
+            lrd.linear_wgrad_batched(dY if tu else None, s["H"] if tu else None, s["dH"] if tv else None, X if tv else None,
+                                     s["dV"], s["dU"], mask, self.ws)
+        q = st["qkv"]
+        if tv:      # the stacked first factors: one product of depth 3r per layer
+            lrd.linear_wgrad_batched(None, None, q["dH"], self.Xs, q["dV"], None, mask | 2, self.ws)
+        if tu:      # the second factors: member g of every layer, addressed inside the stacks
+            for g in range(3):
+                lrd.linear_wgrad_batched(self.dqkv[:, g], q["H"][:, :, g * r:(g + 1) * r], None, None, None, q["dU_by_member"][g],
+                                         mask | 1, self.ws)
 
     def step(self, mask):
         self.forward()
@@ -866,6 +910,8 @@ def main():
     ap.add_argument("--no-comparators", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
     ap.add_argument("--no-workloads", action="store_true", help="skip the other workloads (FFN stack, rank sweep points, Tucker stages)")
+    ap.add_argument("--per-layer-backward", action="store_true",
+                    help="headline with one backward call per layer instead of batched weight gradients")
     ap.add_argument("--no-peaks", action="store_true", help="skip the in-run peak measurements")
     ap.add_argument("--rank-sweep", action="store_true", help="run the rank sweep (config 3) instead of the FFN stack")
     ap.add_argument("--rank-search", action="store_true",
@@ -984,11 +1030,11 @@ def kernel_roofline(rows):
     flops = nbytes = 0.0
     shapes = {}
     for r in grp:
-        M, N, K = r["M"], r["N"], r["K"]
+        M, N, K, nb = r["M"], r["N"], r["K"], max(1, r.get("batch", 1))
         out_b = 4 if r["role"] in (5, 6) or "f32" in r["kernel"] else 2
-        nbytes += 2 * (M * K + N * K) + out_b * M * N + (2 * M * N if r["epilogue"] else 0)
-        flops += 2.0 * M * N * K
-        key = f"{M}x{N}x{K}" + ("+act" if r["epilogue"] else "")
+        nbytes += nb * (2 * (M * K + N * K) + out_b * M * N + (2 * M * N if r["epilogue"] else 0))
+        flops += 2.0 * M * N * K * nb
+        key = (f"{nb} x " if nb > 1 else "") + f"{M}x{N}x{K}" + ("+act" if r["epilogue"] else "")
         shapes[key] = shapes.get(key, 0) + 1
     t_mfma, t_hbm = flops / (MFMA_BF16_PEAK_TFLOPS * 1e12), nbytes / (HBM_PEAK_GBS * 1e9)
     n = len(grp)
@@ -1016,7 +1062,8 @@ def graph_or_eager(torch, step_for_parity, steps, warmup, use_graph):
 def headline(args, torch, np, si, lrd):
     peaks = None if args.no_peaks else measure_peaks(torch, lrd)
     rank = lrd.quantize_rank(ENC_RANK, 64)
-    enc = Encoder(lrd, torch, np, si, rank, seed_stream=0)
+    deferred = not args.per_layer_backward
+    enc = Encoder(lrd, torch, np, si, rank, seed_stream=0, deferred=deferred)
     masks = (lrd.freeze_mask(lrd.KIND_SVD, 0), lrd.freeze_mask(lrd.KIND_SVD, 1))
 
     def one(s):
@@ -1053,8 +1100,9 @@ def headline(args, torch, np, si, lrd):
             torch.cuda.synchronize()
 
             def snapshot():
-                L = enc.layers[0]
-                return [t.clone() for t in (enc.X[enc.n_layers], enc.gX[1], L["up"]["dU"], L["up"]["dV"], L["qkv"]["dU"], L["qkv"]["dV"])]
+                s = enc.st
+                return [t.clone() for t in (enc.X[enc.n_layers], enc.G[0], s["up"]["dU"], s["up"]["dV"], s["dn"]["dU"], s["o"]["dV"],
+                                            s["qkv"]["dU"], s["qkv"]["dU_by_member"], s["qkv"]["dV"])]
 
             graph_ok = True
             for rep in range(2):
@@ -1062,7 +1110,7 @@ def headline(args, torch, np, si, lrd):
                     one(parity)
                     torch.cuda.synchronize()
                     want = snapshot()
-                    for t in (enc.X[enc.n_layers], enc.gX[1]):
+                    for t in (enc.X[enc.n_layers], enc.G[0]):
                         t.zero_()
                     graphs[parity].replay()
                     torch.cuda.synchronize()
@@ -1093,6 +1141,8 @@ def headline(args, torch, np, si, lrd):
                config=dict(workload="config 5: 12-layer transformer encoder, hidden 1024, 16 heads, FFN 4096, seq 512 x batch 16 = 8192 tokens, "
                                     "bf16; all Q/K/V/O and FFN linears SVD-decomposed at quantized rank 256, sequential freezing by step "
                                     "parity; decomposed-linear kernels only (attention, layer norm, residuals not run)",
+                           backward="data gradients layer by layer, then the weight gradients of the 12 layers of each shape in one launch"
+                                    if deferred else "one call per layer (data and weight gradients)",
                            tokens=ENC_T, rank=rank, layers=ENC_LAYERS, hidden=ENC_D, ffn=ENC_FF),
                tokens_per_s=ENC_T / (ms * 1e-3), frac_bf16_mfma_peak=tflops / MFMA_BF16_PEAK_TFLOPS,
                binding_roof=dict(roof_ms_per_step=roof * 1e-3, frac=roof * 1e-3 / ms,
@@ -1122,12 +1172,26 @@ def headline(args, torch, np, si, lrd):
         u_ms = graph_or_eager(torch, lambda parity: unfrozen.step(0), k, 2, graph_ok)
         del unfrozen
         torch.cuda.empty_cache()
+        # the freezing ratio is taken between two runs on the headline's own schedule
+        unfrozen = Encoder(lrd, torch, np, si, rank, seed_stream=1, deferred=deferred)
+        ud_ms = graph_or_eager(torch, lambda parity: unfrozen.step(0), k, 2, graph_ok) if deferred else u_ms
+        del unfrozen
+        torch.cuda.empty_cache()
+        per_layer = Encoder(lrd, torch, np, si, rank, seed_stream=0)
+        pl_ms = graph_or_eager(torch, lambda parity: per_layer.step(masks[parity]), k, 2, graph_ok) if deferred else ms
+        del per_layer
+        torch.cuda.empty_cache()
         out["comparators"] = dict(dense_ms_per_step=d_ms, dense_tflops=d_tflops, dense_frac_bf16_mfma_peak=d_tflops / MFMA_BF16_PEAK_TFLOPS,
                                   speedup_vs_dense=d_ms / ms,
                                   vanilla_rank=raw_rank, vanilla_unfrozen_ms_per_step=v_ms, quantized_unfrozen_ms_per_step=u_ms,
-                                  speedup_rank_quantization=v_ms / u_ms, speedup_freezing=u_ms / ms, speedup_combined=v_ms / ms,
-                                  note="vanilla = raw rank 257 (Section 2.1's 257 -> 256 example), nothing frozen, Q/K/V as three separate layers; comparators are "
-                                       "launched the same way as the headline (%s)" % ("hip-graph replay" if graph_ok else "eager"))
+                                  quantized_unfrozen_batched_wgrad_ms_per_step=ud_ms, frozen_per_layer_backward_ms_per_step=pl_ms,
+                                  speedup_rank_quantization=v_ms / u_ms, speedup_freezing=ud_ms / ms, speedup_batched_wgrad=pl_ms / ms,
+                                  speedup_combined=v_ms / ms,
+                                  note="vanilla = raw rank 257 (Section 2.1's 257 -> 256 example), nothing frozen, Q/K/V as three separate layers, "
+                                       "one backward call per layer; rank quantization compares it with rank 256 on that same per-layer schedule; "
+                                       "freezing compares unfrozen and frozen on the headline's schedule; dense layers run their (large) weight "
+                                       "gradients per layer; comparators are launched the same way as the headline (%s)"
+                                       % ("hip-graph replay" if graph_ok else "eager"))
     if not args.no_workloads:
         out["workloads"] = other_workloads(args, torch, np, si, lrd, graph_ok)
     if not args.no_cpu_baseline:

@@ -243,6 +243,43 @@ lrd_status lrd_linear_group_bwd(const void* dY, const void* X, const void* H, co
                                 void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * The backward pass of a stack of equal layers in two parts, for callers that keep every layer's
+ * gradient input and saved activations until the stack's backward has finished (sizes here make that
+ * cheap).  The weight gradients of Section 2 (dU = dY^T.H, dV = dH^T.X) are small products with a
+ * long reduction over the tokens: one layer's does not fill the device, the same product for all the
+ * layers of one shape, as one launch, does, and needs no sliced reduction.
+ *   lrd_linear_bwd_data / lrd_linear_group_bwd_data: only the data gradient, dX = (dY.U).V (times
+ *     act'(Z_in) as in lrd_linear_bwd_act).  dH_save [T x r] ([T x groups*r] for a group), dtype dt,
+ *     caller's, required, receives dH = dY.U, which the first factor's gradient needs later; dX may
+ *     be NULL (first layer of a network: only dH is formed).  Workspace from lrd_linear_workspace_bytes /
+ *     lrd_linear_group_workspace_bytes.  Results are bit-identical to lrd_linear_bwd(_act) /
+ *     lrd_linear_group_bwd with both factors frozen (bf16 ranks that are not multiples of 8 aside:
+ *     only the one-call form pads them).
+ *   lrd_linear_wgrad_batched: for l = 0 .. layers-1, dU[l] = dY[l]^T.H[l] (unless LRD_FREEZE_L1) and
+ *     dV[l] = dH[l]^T.X[l] (unless LRD_FREEZE_L0).  Layer l's operand starts l * stride elements
+ *     after the base pointer (strides multiples of 8 elements): dY [T x out] rows dense; H [T x r]
+ *     with row pitch ldh; dH [T x r] with row pitch lddh; X [T x in] rows dense.  The row pitches
+ *     let a group's side-by-side intermediates be addressed in place: one call per group member for
+ *     dU (base pointer g*r elements in, ldh = groups*r), and one call with r := groups*r for the
+ *     stacked first factors.  dU [layers][out x r] and dV [layers][r x in] are fp32, dense,
+ *     overwritten.  Operands of a frozen factor may be NULL.  Results equal `layers` calls of
+ *     lrd_linear_bwd up to the order of the sum over tokens (both are fixed, so each is
+ *     reproducible).
+ */
+lrd_status lrd_linear_bwd_data(const void* dY, const void* V, const void* U, void* dX, void* dH_save,
+                               const void* Z_in, int32_t act, int64_t T, int64_t in, int64_t out, int64_t r,
+                               lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream);
+lrd_status lrd_linear_group_bwd_data(const void* dY, const void* V_cat, const void* U, void* dX, void* dH_save,
+                                     int64_t T, int64_t in, int64_t out, int64_t r, int32_t groups, lrd_dtype dt,
+                                     void* ws, size_t ws_bytes, void* hip_stream);
+size_t lrd_linear_wgrad_batched_workspace_bytes(int64_t layers, int64_t T, int64_t in, int64_t out, int64_t r,
+                                                lrd_dtype dt, uint32_t freeze_mask);
+lrd_status lrd_linear_wgrad_batched(const void* dY, int64_t dy_stride, const void* H, int64_t ldh, int64_t h_stride,
+                                    const void* dH, int64_t lddh, int64_t dh_stride, const void* X, int64_t x_stride,
+                                    float* dV, float* dU, uint32_t freeze_mask, int64_t layers, int64_t T, int64_t in,
+                                    int64_t out, int64_t r, lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
  * The same two calls with the activation between stacked layers folded into them (GELU, erf
  * form; not part of the paper's method, it removes two elementwise passes of a layer stack).
  *   lrd_linear_fwd_act: Y receives the pre-activation Z = H.U^T (+ bias), which the backward

@@ -59,6 +59,7 @@ typedef struct {
     int32_t epilogue;         /* 0 none, 1 activation stored beside the result, 2 result times activation gradient */
     int32_t splits;           /* slices of the reduction (1: one kernel) */
     int64_t M, N, K;          /* result M x N, reduction length K */
+    int64_t batch;            /* products of this shape the launch ran (1 unless batched) */
     char kernel[64];          /* the kernel that ran the product (template and tile), NUL-terminated */
 } lrd_profile_record;
 lrd_status lrd_profile_log_start(void** events, int32_t n_pairs);

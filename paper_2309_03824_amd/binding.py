@@ -28,6 +28,7 @@ EXPORTS = (
     "lrd_status_string", "lrd_quantize_rank", "lrd_freeze_mask", "lrd_tucker_rank", "lrd_svd_rank", "lrd_select_rank",
     "lrd_sgd_step", "lrd_linear_sgd_workspace_bytes", "lrd_linear_bwd_sgd",
     "lrd_linear_group_workspace_bytes", "lrd_linear_group_fwd", "lrd_linear_group_bwd",
+    "lrd_linear_bwd_data", "lrd_linear_group_bwd_data", "lrd_linear_wgrad_batched_workspace_bytes", "lrd_linear_wgrad_batched",
     "lrd_svd_factors_workspace_bytes", "lrd_svd_factors", "lrd_svd_factors_batched_workspace_bytes", "lrd_svd_factors_batched", "lrd_tucker2_factors_workspace_bytes", "lrd_tucker2_factors",
     "lrd_linear_workspace_bytes", "lrd_linear_fwd", "lrd_linear_bwd", "lrd_linear_fwd_act", "lrd_linear_bwd_act",
     "lrd_linear_bwd_static", "lrd_linear_bwd_static_fits",
@@ -53,7 +54,7 @@ class Sgd(Structure):
 
 class ProfileRecord(Structure):
     _fields_ = [("role", c_int32), ("gather", c_int32), ("epilogue", c_int32), ("splits", c_int32),
-                ("M", c_int64), ("N", c_int64), ("K", c_int64), ("kernel", ctypes.c_char * 64)]
+                ("M", c_int64), ("N", c_int64), ("K", c_int64), ("batch", c_int64), ("kernel", ctypes.c_char * 64)]
 
 
 class ConvGeom(Structure):
@@ -120,6 +121,14 @@ def _load() -> ctypes.CDLL:
     lib.lrd_linear_group_workspace_bytes.argtypes = [I64] * 4 + [c_int32, ctypes.c_int, U32]
     lib.lrd_linear_group_fwd.restype = ctypes.c_int
     lib.lrd_linear_group_fwd.argtypes = [P] * 6 + [I64] * 4 + [c_int32, ctypes.c_int, P, SZ, P]
+    lib.lrd_linear_bwd_data.restype = ctypes.c_int
+    lib.lrd_linear_bwd_data.argtypes = [P] * 6 + [c_int32] + [I64] * 4 + [ctypes.c_int, P, SZ, P]
+    lib.lrd_linear_group_bwd_data.restype = ctypes.c_int
+    lib.lrd_linear_group_bwd_data.argtypes = [P] * 5 + [I64] * 4 + [c_int32, ctypes.c_int, P, SZ, P]
+    lib.lrd_linear_wgrad_batched_workspace_bytes.restype = SZ
+    lib.lrd_linear_wgrad_batched_workspace_bytes.argtypes = [I64] * 5 + [ctypes.c_int, U32]
+    lib.lrd_linear_wgrad_batched.restype = ctypes.c_int
+    lib.lrd_linear_wgrad_batched.argtypes = [P, I64, P, I64, I64, P, I64, I64, P, I64, P, P, U32] + [I64] * 5 + [ctypes.c_int, P, SZ, P]
     lib.lrd_linear_group_bwd.restype = ctypes.c_int
     lib.lrd_linear_group_bwd.argtypes = [P] * 9 + [U32] + [I64] * 4 + [c_int32, ctypes.c_int, P, SZ, P]
     lib.lrd_linear_fwd_act.restype = ctypes.c_int
@@ -371,7 +380,7 @@ class ProfileLog:
         out = []
         for i in range(min(self.count, self.n)):
             r = self.records[i]
-            out.append(dict(role=r.role, gather=r.gather, epilogue=r.epilogue, splits=r.splits, M=r.M, N=r.N, K=r.K,
+            out.append(dict(role=r.role, gather=r.gather, epilogue=r.epilogue, splits=r.splits, M=r.M, N=r.N, K=r.K, batch=r.batch,
                             kernel=r.kernel.decode(), us=self.events[2 * i].elapsed_us(self.events[2 * i + 1])))
         return out
 
@@ -459,6 +468,58 @@ def linear_group_bwd(dY, X, H, V_cat, U, dX, dV_cat, dU, dbias, freeze_mask, ws=
     _check(_lib.lrd_linear_group_bwd(_ptr(dY), _ptr(X), _ptr(H), _ptr(V_cat), _ptr(U), _ptr(dX), _ptr(dV_cat), _ptr(dU),
                                      _ptr(dbias), freeze_mask, T, n_in, n_out, r, G, _dt(dY), wp, wb, _stream(stream)),
            "lrd_linear_group_bwd")
+
+
+def linear_bwd_data(dY, V, U, dX, dH_save, Z_in=None, act=0, ws=None, stream=None):
+    """Data gradient only; dH_save [T x r] receives dY.U for a later lrd_linear_wgrad_batched."""
+    T, n_out = dY.shape
+    r, n_in = V.shape
+    assert U.shape == (n_out, r) and (dX is None or dX.shape == (T, n_in)) and dH_save.shape == (T, r)
+    wp, wb = _ws(ws)
+    _check(_lib.lrd_linear_bwd_data(_ptr(dY), _ptr(V), _ptr(U), _ptr(dX), _ptr(dH_save), _ptr(Z_in), act, T, n_in, n_out, r,
+                                    _dt(dY), wp, wb, _stream(stream)), "lrd_linear_bwd_data")
+
+
+def linear_group_bwd_data(dY, V_cat, U, dX, dH_save, ws=None, stream=None):
+    G, T, n_out = dY.shape
+    r, n_in = U.shape[2], V_cat.shape[1]
+    assert dH_save.shape == (T, G * r) and (dX is None or dX.shape == (T, n_in))
+    wp, wb = _ws(ws)
+    _check(_lib.lrd_linear_group_bwd_data(_ptr(dY), _ptr(V_cat), _ptr(U), _ptr(dX), _ptr(dH_save), T, n_in, n_out, r, G,
+                                          _dt(dY), wp, wb, _stream(stream)), "lrd_linear_group_bwd_data")
+
+
+def linear_wgrad_batched_workspace_bytes(layers, T, n_in, n_out, r, dtype, freeze_mask=0) -> int:
+    return int(_lib.lrd_linear_wgrad_batched_workspace_bytes(layers, T, n_in, n_out, r, dtype, freeze_mask))
+
+
+def linear_wgrad_batched(dY, H, dH, X, dV, dU, freeze_mask, ws=None, stream=None):
+    """dU[l] = dY[l]^T.H[l], dV[l] = dH[l]^T.X[l] for stacks [layers][T][.]; H and dH may be column
+    slices of wider stacks (their row pitch and layer stride are taken from the tensor strides)."""
+    ref = dY if dY is not None else dH
+    L, T = ref.shape[0], ref.shape[1]
+    n_out = dU.shape[1] if dU is not None else 0
+    n_in = dV.shape[2] if dV is not None else 0
+    r = dU.shape[2] if dU is not None else dV.shape[1]
+    dt = _dt(ref)
+
+    def pitch(t, cols):
+        if t is None:
+            return 0, 0
+        assert t.shape == (L, T, cols) and t.stride(2) == 1, (tuple(t.shape), (L, T, cols))
+        return t.stride(1), (t.stride(0) if L > 1 else 0)
+
+    ldy, sy = pitch(dY, n_out)
+    ldh, sh = pitch(H, r)
+    lddh, sdh = pitch(dH, r)
+    ldx, sx = pitch(X, n_in)
+    assert (dY is None or ldy == n_out) and (X is None or ldx == n_in)
+    n_out = n_out or 1
+    n_in = n_in or 1
+    wp, wb = _ws(ws)
+    at = lambda t: None if t is None else t.data_ptr()   # slices of wider stacks: pitch and stride say where
+    _check(_lib.lrd_linear_wgrad_batched(at(dY), sy, at(H), ldh or r, sh, at(dH), lddh or r, sdh, at(X), sx, _ptr(dV), _ptr(dU),
+                                         freeze_mask, L, T, n_in, n_out, r, dt, wp, wb, _stream(stream)), "lrd_linear_wgrad_batched")
 
 
 def linear_fwd_act(X, V, U, bias, Y, Y_act, H_save, act, ws=None, stream=None):

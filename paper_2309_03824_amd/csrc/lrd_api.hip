@@ -33,7 +33,7 @@ hipError_t run_chain(const ChainOp& ch, hipStream_t st)
     hipError_t e = mfma_chain(ch, st);
     if (logged >= 0) {
         (void)hipEventRecord(ev1, st);
-        log_end(logged, ch.role, 0, 0, 1, ch.M, ch.N2, ch.K1);
+        log_end(logged, ch.role, 0, 0, 1, ch.M, ch.N2, ch.K1, 1);
     }
     return e;
 }
@@ -651,6 +651,148 @@ lrd_status lrd_linear_group_bwd(const void* dY, const void* X, const void* H, co
     if (dbias)
         for (int32_t g = 0; g < groups; ++g)
             LRD_TRY(column_sums(at(dY, (int64_t)g * T * out, dt), dbias + (int64_t)g * out, T, out, dt == LRD_BF16, st));
+    return LRD_OK;
+}
+
+// ------------------------------------------------------------------------------------ deferred weight gradients
+lrd_status lrd_linear_bwd_data(const void* dY, const void* V, const void* U, void* dX, void* dH_save, const void* Z_in,
+                               int32_t act, int64_t T, int64_t in, int64_t out, int64_t r, lrd_dtype dt, void* ws,
+                               size_t ws_bytes, void* hip_stream)
+{
+    if (!dtype_ok(dt) || !linear_dims_ok(T, in, out, r) || !dY || !V || !U || !dH_save) return LRD_ERR_INVALID_ARG;
+    if ((act != LRD_ACT_NONE && act != LRD_ACT_GELU) || (act == LRD_ACT_GELU && dX && !Z_in)) return LRD_ERR_INVALID_ARG;
+    if (act == LRD_ACT_NONE || !dX) Z_in = nullptr;
+    if (!aligned16(dY) || !aligned16(V) || !aligned16(U) || !aligned16(dX) || !aligned16(dH_save) || !aligned16(Z_in) ||
+        !aligned16(ws))
+        return LRD_ERR_ALIGNMENT;
+    hipStream_t st = (hipStream_t)hip_stream;
+    Carver cv(ws, ws_bytes);
+    const size_t region_bytes = act_partial_bytes(T, r, out, dt);
+    void* region = region_bytes ? cv.take(region_bytes) : nullptr;
+    if (!cv.ok) return LRD_ERR_WORKSPACE;
+    MatOp d1 = nn(dY, out, U, r, dH_save, r, T, r, out, dt);
+    d1.role = LRD_ROLE_DGRAD_UP;
+    share_splits(d1, region, dt, SPLIT_ACT);
+    LRD_TRY(run_matop(d1, st));
+    if (!dX) return LRD_OK;
+    MatOp d2 = nn(dH_save, r, V, in, dX, in, T, in, r, dt);
+    d2.role = LRD_ROLE_DGRAD_DOWN;
+    if (Z_in) {
+        if (dt == LRD_BF16 && in % 8 == 0) {
+            d2.epilogue = EPI_ACT_GRAD;
+            d2.aux = const_cast<void*>(Z_in);
+            d2.ldaux = in;
+            LRD_TRY(run_matop(d2, st));
+        } else {
+            LRD_TRY(run_matop(d2, st));
+            LRD_TRY(gelu_bwd(dX, Z_in, dX, T * in, dt == LRD_BF16, st));
+        }
+    } else {
+        LRD_TRY(run_matop(d2, st));
+    }
+    return LRD_OK;
+}
+
+lrd_status lrd_linear_group_bwd_data(const void* dY, const void* V_cat, const void* U, void* dX, void* dH_save, int64_t T,
+                                     int64_t in, int64_t out, int64_t r, int32_t groups, lrd_dtype dt, void* ws,
+                                     size_t ws_bytes, void* hip_stream)
+{
+    if (!dtype_ok(dt) || !group_dims_ok(T, in, out, r, groups) || !dY || !V_cat || !U || !dH_save) return LRD_ERR_INVALID_ARG;
+    if (!aligned16(dY) || !aligned16(V_cat) || !aligned16(U) || !aligned16(dX) || !aligned16(dH_save) || !aligned16(ws))
+        return LRD_ERR_ALIGNMENT;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int64_t gr = (int64_t)groups * r;
+    Carver cv(ws, ws_bytes);
+    const size_t region_bytes = act_partial_bytes(T, r, out, dt);
+    void* region = region_bytes ? cv.take(region_bytes) : nullptr;
+    if (!cv.ok) return LRD_ERR_WORKSPACE;
+    if (choose_splits_act(T, r, out, dt == LRD_BF16) > 1) {
+        for (int32_t g = 0; g < groups; ++g) {
+            MatOp d1 = nn(at(dY, (int64_t)g * T * out, dt), out, at(U, (int64_t)g * out * r, dt), r, (void*)at(dH_save, g * r, dt),
+                          gr, T, r, out, dt);
+            d1.role = LRD_ROLE_DGRAD_UP;
+            share_splits(d1, region, dt, SPLIT_ACT);
+            LRD_TRY(run_matop(d1, st));
+        }
+    } else {
+        MatOp d1 = nn(dY, out, U, r, dH_save, gr, T, r, out, dt);
+        d1.role = LRD_ROLE_DGRAD_UP;
+        d1.batch = groups;
+        d1.a_bs = T * out; d1.b_bs = out * r; d1.c_bs = r;
+        LRD_TRY(run_matop(d1, st));
+    }
+    if (dX) {
+        MatOp d2 = nn(dH_save, gr, V_cat, in, dX, in, T, in, gr, dt);
+        d2.role = LRD_ROLE_DGRAD_DOWN;
+        LRD_TRY(run_matop(d2, st));
+    }
+    return LRD_OK;
+}
+
+namespace {
+inline bool wgrad_batched_dims_ok(int64_t layers, int64_t T, int64_t in, int64_t out, int64_t r)
+{
+    return layers >= 1 && layers <= 1024 && T >= 1 && in >= 1 && out >= 1 && r >= 1 && T < (int64_t(1) << 31) &&
+           in < (int64_t(1) << 24) && out < (int64_t(1) << 24) && r < (int64_t(1) << 24);
+}
+inline size_t batched_partial_bytes(int64_t M, int64_t N, int64_t K, int64_t batch)
+{
+    const int s = choose_splits_batched(M, N, K, batch);
+    return s > 1 ? round256((size_t)s * (size_t)batch * (size_t)M * (size_t)N * sizeof(float)) : 0;
+}
+}  // namespace
+
+size_t lrd_linear_wgrad_batched_workspace_bytes(int64_t layers, int64_t T, int64_t in, int64_t out, int64_t r, lrd_dtype dt,
+                                                uint32_t freeze_mask)
+{
+    if (!dtype_ok(dt) || !wgrad_batched_dims_ok(layers, T, in, out, r)) return 0;
+    size_t b = 0;
+    if (!(freeze_mask & LRD_FREEZE_L1)) b = std::max(b, batched_partial_bytes(out, r, T, layers));
+    if (!(freeze_mask & LRD_FREEZE_L0)) b = std::max(b, batched_partial_bytes(r, in, T, layers));
+    return b;
+}
+
+lrd_status lrd_linear_wgrad_batched(const void* dY, int64_t dy_stride, const void* H, int64_t ldh, int64_t h_stride,
+                                    const void* dH, int64_t lddh, int64_t dh_stride, const void* X, int64_t x_stride, float* dV,
+                                    float* dU, uint32_t freeze_mask, int64_t layers, int64_t T, int64_t in, int64_t out, int64_t r,
+                                    lrd_dtype dt, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    if (!dtype_ok(dt) || !wgrad_batched_dims_ok(layers, T, in, out, r)) return LRD_ERR_INVALID_ARG;
+    if (freeze_mask & ~uint32_t(LRD_FREEZE_L0 | LRD_FREEZE_L1)) return LRD_ERR_INVALID_ARG;
+    const bool train_v = !(freeze_mask & LRD_FREEZE_L0), train_u = !(freeze_mask & LRD_FREEZE_L1);
+    if (train_u && (!dY || !H || !dU || ldh < r || dy_stride % 8 || h_stride % 8 || dy_stride < 0 || h_stride < 0))
+        return LRD_ERR_INVALID_ARG;
+    if (train_v && (!dH || !X || !dV || lddh < r || dh_stride % 8 || x_stride % 8 || dh_stride < 0 || x_stride < 0))
+        return LRD_ERR_INVALID_ARG;
+    if (!aligned16(ws) || (train_u && (!aligned16(dY) || !aligned16(H) || !aligned16(dU))) ||
+        (train_v && (!aligned16(dH) || !aligned16(X) || !aligned16(dV))))
+        return LRD_ERR_ALIGNMENT;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const size_t region_bytes = lrd_linear_wgrad_batched_workspace_bytes(layers, T, in, out, r, dt, freeze_mask);
+    if (region_bytes > ws_bytes || (region_bytes && !ws)) return LRD_ERR_WORKSPACE;
+    auto slice = [&](MatOp& op) {
+        const int s = choose_splits_batched(op.M, op.N, op.K, layers);
+        if (s > 1) {
+            op.partial = (float*)ws;
+            op.splits = s;
+        }
+    };
+    if (train_u) {
+        MatOp wu = tn(dY, out, H, ldh, dU, r, out, r, T, dt);
+        wu.role = LRD_ROLE_WGRAD_U;
+        wu.batch = (int)layers;
+        wu.a_bs = dy_stride; wu.b_bs = h_stride; wu.c_bs = out * r;
+        slice(wu);
+        LRD_TRY(run_matop(wu, st));
+    }
+    if (train_v) {
+        MatOp wv = tn(dH, lddh, X, in, dV, in, r, in, T, dt);
+        wv.role = LRD_ROLE_WGRAD_V;
+        wv.batch = (int)layers;
+        wv.a_bs = dh_stride; wv.b_bs = x_stride; wv.c_bs = r * in;
+        slice(wv);
+        LRD_TRY(run_matop(wv, st));
+    }
     return LRD_OK;
 }
 

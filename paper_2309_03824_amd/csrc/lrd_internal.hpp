@@ -83,6 +83,7 @@ hipError_t apply_epilogue(const MatOp& op, hipStream_t st);        // unfused fo
 int choose_splits(int64_t M, int64_t N, int64_t K, bool in_bf16);
 // Split-K count for a product whose result is a narrow bf16 activation (1 = not split).
 int choose_splits_act(int64_t M, int64_t N, int64_t K, bool in_bf16);
+int choose_splits_batched(int64_t M, int64_t N, int64_t K, int64_t batch);
 
 // Fused pair  C2[M x N2] = (A[M x K1] . B1[R x K1]^T) . B2[N2 x R]^T : the rank-R intermediate
 // stays on chip; optionally it is also stored (mid_save, [M x R], operand dtype).
@@ -103,7 +104,7 @@ hipError_t mfma_chain(const ChainOp& op, hipStream_t st);
 // next record, or returns a negative index when logging is off or the events have run out; log_end
 // fills the record.  note_kernel is called by a launcher with the name of the kernel it launched.
 int log_begin(hipEvent_t* start, hipEvent_t* stop);
-void log_end(int index, int role, int gather, int epilogue, int splits, int64_t M, int64_t N, int64_t K);
+void log_end(int index, int role, int gather, int epilogue, int splits, int64_t M, int64_t N, int64_t K, int64_t batch = 1);
 void note_kernel(const char* name);
 
 // Elementwise / reductions.

@@ -161,3 +161,46 @@ def test_dense_conv_full_batch():
         check(host(Y_), oracle.conv_fwd(Xo, Wo, 1, 1), DT, "Y")
         check(host(gX), oracle.conv_dgrad(dYo, Wo, (hw, hw), 1, 1), DT, "dX")
         check(host(gW), oracle.conv_wgrad(dYo, Xo, k, 1, 1), DT, "dW")
+
+
+@pytest.mark.parametrize("n_in,n_out,mask", [(1024, 4096, 1), (4096, 1024, 2), (1024, 1024, 1), (1024, 1024, 2)])
+def test_deferred_weight_gradients_of_the_encoder_stack(n_in, n_out, mask):
+    """Weight gradients of the 12 encoder layers of one shape in one call (rank 256, 8192 tokens, dense
+    gradients): every layer against the one-call backward, two layers against the oracle on sampled
+    components over all tokens.  Layer l's operands are the seeded base tensors rolled by 37 * l rows."""
+    L, T, r = 12, 8192, 256
+    rng = si.rng_for(3, 8000 + n_in // 256 + n_out // 128 + mask)
+    X0, dY0 = si.gaussian((T, n_in), rng), si.gaussian((T, n_out), rng)
+    U, V = si.direct_factors(n_out, n_in, r, rng)
+    X0_, dY0_, U_, V_ = dev(X0, DT), dev(dY0, DT), dev(U, DT), dev(V, DT)
+    X_ = torch.stack([torch.roll(X0_, 37 * l, 0) for l in range(L)])
+    dY_ = torch.stack([torch.roll(dY0_, -37 * l, 0) for l in range(L)])
+    H_, dH_, gX = empty((L, T, r), DT), empty((L, T, r), DT), empty((T, n_in), DT)
+    Y_ = empty((T, n_out), DT)
+    ws = workspace(max(lrd.linear_workspace_bytes(T, n_in, n_out, r, lrd.BF16, 0),
+                       lrd.linear_wgrad_batched_workspace_bytes(L, T, n_in, n_out, r, lrd.BF16, mask)))
+    for l in range(L):
+        lrd.linear_fwd(X_[l], V_, U_, None, Y_, H_[l], ws)
+        lrd.linear_bwd_data(dY_[l], V_, U_, gX, dH_[l], None, lrd.ACT_NONE, ws)
+    gV, gU = f32((L, r, n_in), -7.0), f32((L, n_out, r), -7.0)
+    lrd.linear_wgrad_batched(None if mask & 2 else dY_, None if mask & 2 else H_, None if mask & 1 else dH_,
+                             None if mask & 1 else X_, gV, gU, mask, ws)
+    torch.cuda.synchronize()
+    got = gV if mask & 2 else gU
+    assert torch.all((gU if mask & 2 else gV) == -7.0)
+    one_v, one_u = f32((r, n_in)), f32((n_out, r))
+    for l in range(L):
+        lrd.linear_bwd(dY_[l], X_[l], H_[l], V_, U_, gX, one_v, one_u, None, mask, ws)
+        check(host(got[l]), host(one_v if mask & 2 else one_u), DT, f"layer {l} against the one-call backward")
+    Xo, dYo, Uo, Vo = seen(X0, DT), seen(dY0, DT), seen(U, DT), seen(V, DT)
+    comp = np.sort(rng.choice(r, size=16, replace=False))
+    cidx = torch.from_numpy(comp).cuda()
+    Vs, Us = np.ascontiguousarray(Vo[comp]), np.ascontiguousarray(Uo[:, comp])
+    for l in (0, 7):
+        Xl, dYl = np.roll(Xo, 37 * l, 0), np.roll(dYo, -37 * l, 0)
+        Hs, _ = oracle.linear_fwd(Xl, Vs, Us)
+        gs = oracle.linear_bwd(dYl, Xl, Hs, Vs, Us, mask, want_dX=False)
+        if mask & 2:
+            check(host(gV[l][cidx]), gs["dV"], DT, f"dV rows, layer {l}")
+        else:
+            check(host(gU[l][:, cidx]), gs["dU"], DT, f"dU columns, layer {l}")
