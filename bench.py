@@ -767,7 +767,8 @@ def rank_search(args, torch, lrd):
         noise = 0.03 * sorted(times)[len(times) // 2]      # differences below 3 % of the median step are jitter
         out = dict(layer=name, r_estimated=r_max, r_min=r_min, dense_us=t_dense, noise_us=noise,
                    t_estimated_us=times[-1], **extra)
-        for label, mode in (("first_peak", lrd.SELECT_FIRST_PEAK), ("argmax", lrd.SELECT_ARGMAX)):
+        for label, mode in (("first_peak", lrd.SELECT_FIRST_PEAK), ("argmax", lrd.SELECT_ARGMAX),
+                            ("first_peak_require_faster", lrd.SELECT_FIRST_PEAK | lrd.SELECT_REQUIRE_FASTER)):
             r_opt, keep = lrd.select_rank(times, r_min, r_max, t_dense, noise, mode)
             out[label] = dict(r_opt=r_opt, keep_decomposed=keep, t_us=times[r_opt - r_min],
                               speedup_vs_estimated=times[-1] / times[r_opt - r_min],
@@ -1020,6 +1021,17 @@ def measure_peaks(torch, lrd):
     return res
 
 
+# HBM bytes per launch of the product kernels as the traffic counters saw them (FETCH_SIZE, WRITE_SIZE per
+# dispatch, scaled by what the same counters read for a plain copy of known size: 2.00 and 1.00), by kernel
+# and product shape; profiles/encoder_step_hbm_traffic.md holds the runs.  Reported only for a kernel and a
+# mix of shapes that were profiled as they are now.
+MIB = float(1 << 20)
+PROFILED_TRAFFIC = {
+    "gemm2_kernel<128,128,2,4,A_KC,B_KC,bf16>": {"8192x4096x256+act": (20.2 + 128.1) * MIB, "3 x 8192x1024x256": (24.2 + 48.0) * MIB,
+                                                 "8192x1024x256": (8.2 + 16.0) * MIB},
+}
+
+
 def kernel_roofline(rows):
     """Roofline object of the product kernel with the largest total time among the logged launches."""
     groups = {}
@@ -1044,7 +1056,12 @@ def kernel_roofline(rows):
     else:
         ach = flops / (total_us * 1e-6) / 1e12
         roof = dict(bound="mfma", achieved=ach, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s", frac=ach / MFMA_BF16_PEAK_TFLOPS)
-    roof.update(traffic=None, kernel=name, avg_us=total_us / n, launches=n, bytes_per_launch=nbytes / n, flops_per_launch=flops / n,
+    seen = PROFILED_TRAFFIC.get(name)
+    traffic = None
+    if seen and all(k in seen for k in shapes):
+        traffic = sum(seen[k] * c for k, c in shapes.items()) / n
+    roof.update(traffic=traffic, traffic_note="HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this command, copy-calibrated "
+                "(profiles/encoder_step_hbm_traffic.md); null when this kernel or its shapes were not the profiled ones", kernel=name, avg_us=total_us / n, launches=n, bytes_per_launch=nbytes / n, flops_per_launch=flops / n,
                 share_of_logged_time=total_us / sum(r["us"] for r in rows), shapes=shapes,
                 note="algorithmic bytes per launch = both operands read once + result written once (+ the activation tensor the "
                      "epilogue writes or reads); duration from HIP events on the launch stream around every launch of this kernel "
@@ -1289,6 +1306,25 @@ def other_workloads(args, torch, np, si, lrd, graph_ok):
                            binding_roof=bound, binding_roof_frac=t_roof / (fwd + bwd), dense_fwd_us=dfw, dense_bwd_us=dbw,
                            speedup_vs_dense=(dfw + dbw) / (fwd + bwd)))
     res["tucker_stages"] = dict(workload="config 4: Tucker-2 3x3 stages, NHWC, N = 128, ranks C/2, fwd + bwd with the core frozen", stages=stages)
+
+    # ---- the pair as two products (H through HBM: the default) against the LDS-staged fused pair, forward and data gradient
+    pairs = []
+    for T_, n_in, n_out, r in ((T_TOKENS, D_MODEL, D_FF, rank2), (ENC_T, ENC_D, ENC_FF, ENC_RANK), (ENC_T, ENC_D, ENC_D, ENC_RANK)):
+        X, dY = rnd(T_, n_in), rnd(T_, n_out)
+        V, U = rnd(r, n_in, scale=n_in ** -0.5), rnd(n_out, r, scale=r ** -0.5)
+        Y, H, dX = torch.empty(T_, n_out, dtype=bf, device="cuda"), torch.empty(T_, r, dtype=bf, device="cuda"), torch.empty(T_, n_in, dtype=bf, device="cuda")
+        ws = torch.empty(lrd.linear_workspace_bytes(T_, n_in, n_out, r, lrd.BF16, 3) + 256, dtype=torch.uint8, device="cuda")
+        row = dict(tokens=T_, n_in=n_in, n_out=n_out, r=r)
+        for name, mode in (("two_products", lrd.FUSION_NEVER), ("fused", lrd.FUSION_ALWAYS)):
+            prev = lrd.set_fusion(mode)
+            try:
+                row[name + "_fwd_us"] = event_us(torch, lambda: lrd.linear_fwd(X, V, U, None, Y, H, ws), 8)
+                row[name + "_dgrad_us"] = event_us(torch, lambda: lrd.linear_bwd(dY, X, H, V, U, dX, None, None, None, 3, ws), 8)
+            finally:
+                lrd.set_fusion(prev)
+        pairs.append(row)
+    res["fused_pair"] = dict(workload="one decomposed linear, forward (H saved) and data gradient (both factors frozen): two products with H / dH "
+                                      "through HBM against one kernel that keeps them in LDS", pairs=pairs)
     return res
 
 

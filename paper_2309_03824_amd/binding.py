@@ -308,7 +308,7 @@ def set_fusion(mode: int) -> int:
 
 
 class HipEvent:
-    """A raw hipEvent_t (created through the HIP runtime), for lrd_profile_next."""
+    """A raw hipEvent_t (created through the HIP runtime), for the product event log."""
     _hip = None
 
     def __init__(self):

@@ -753,7 +753,10 @@ hipError_t by_tile(const MatOp& op, const Operand& A, const Operand& B, hipStrea
     if constexpr (G == GATHER_NONE && ((sizeof(OutT) == 2 && !A_KM) || (sizeof(OutT) == 4 && A_KM && B_KM))) {
         // (a batch of weight gradients: from 128 tiles on, 213 against 368 us for 36 x [1024 x 256] over 8192 tokens)
         const int64_t enough = (sizeof(OutT) == 4 && op.batch >= 8) ? 128 : 224;
-        if (op.K >= 1024 && wgs(256, 256) >= enough) return launch<256, 256, 2, 4, 2, A_KM, B_KM, OutT>(op, A, B, st);
+        // (not for results that fill less than two thirds of their 256 x 256 tiles: the 32 x 64 weight gradient of a
+        // 1x1 convolution has thousands of K-slices and would multiply 32 times its size)
+        const bool fills = 3 * op.M * op.N >= 2 * ceil_div(op.M, 256) * ceil_div(op.N, 256) * 65536;
+        if (op.K >= 1024 && fills && wgs(256, 256) >= enough) return launch<256, 256, 2, 4, 2, A_KM, B_KM, OutT>(op, A, B, st);
     }
     // Results at most 32 columns wide (1x1 and core convolutions at Tucker ranks <= 32): a 128 x 32 tile
     // does a quarter of the MFMA and LDS work of a 128 x 128 one (15 against 23 us at 401408 x 32 x 64).
