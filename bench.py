@@ -49,42 +49,53 @@ def layer_flops(T, n_in, n_out, r, mask, want_dx=True):
 
 
 class Stack:
-    """Buffers and factors of the 12-block stack; fwd/bwd through the library only."""
+    """Buffers and factors of the 12-block stack; fwd/bwd through the library only.  deferred=True runs the
+    backward in two parts (data gradients per block, then each of the two layer shapes' weight gradients
+    for all blocks in one call); the per-block tensors are slices of stacks over the blocks."""
 
-    def __init__(self, lrd, torch, np, si, factorize, rank, seed_stream, true_svd=True):
-        self.lrd, self.torch = lrd, torch
+    def __init__(self, lrd, torch, np, si, factorize, rank, seed_stream, true_svd=True, deferred=False):
+        self.lrd, self.torch, self.deferred = lrd, torch, deferred
         dev = "cuda"
         bf = torch.bfloat16
         rng = si.rng_for(2, seed_stream)
         self.r = rank
         self.layers = []
-        T = T_TOKENS
+        T, NB = T_TOKENS, N_BLOCKS
 
         def to_dev(a):
             bits = si.bf16_bits(a).view(np.int16)
             return torch.from_numpy(bits).to(dev).view(bf).reshape(a.shape)
 
-        for b in range(N_BLOCKS):
+        def empty(*shape, dt=bf):
+            return torch.empty(shape, dtype=dt, device=dev)
+
+        dims = ((D_MODEL, D_FF), (D_FF, D_MODEL))
+        self.st = [dict(H=empty(NB, T, rank), dH=empty(NB, T, rank), dU=empty(NB, n_out, rank, dt=torch.float32),
+                        dV=empty(NB, rank, n_in, dt=torch.float32)) for (n_in, n_out) in dims]
+        for b in range(NB):
             blk = []
-            for (n_in, n_out) in ((D_MODEL, D_FF), (D_FF, D_MODEL)):
+            for i, (n_in, n_out) in enumerate(dims):
                 if true_svd:
                     W = si.linear_weight(n_out, n_in, rng)
                     U, V, _ = factorize.svd_factors(W, rank)
                 else:
                     U, V = si.direct_factors(n_out, n_in, rank, rng)
-                blk.append(dict(n_in=n_in, n_out=n_out, U=to_dev(U), V=to_dev(V),
-                                H=torch.empty((T, rank), dtype=bf, device=dev),
-                                dU=torch.empty((n_out, rank), dtype=torch.float32, device=dev),
-                                dV=torch.empty((rank, n_in), dtype=torch.float32, device=dev)))
+                s = self.st[i]
+                blk.append(dict(n_in=n_in, n_out=n_out, U=to_dev(U), V=to_dev(V), H=s["H"][b], dH=s["dH"][b], dU=s["dU"][b],
+                                dV=s["dV"][b]))
             self.layers.append(blk)
-        self.X = [to_dev(si.gaussian((T, D_MODEL), rng))]
-        self.X += [torch.empty((T, D_MODEL), dtype=bf, device=dev) for _ in range(N_BLOCKS)]
-        self.Z = [torch.empty((T, D_FF), dtype=bf, device=dev) for _ in range(N_BLOCKS)]
-        self.A = [torch.empty((T, D_FF), dtype=bf, device=dev) for _ in range(N_BLOCKS)]
-        self.gX = [torch.empty((T, D_MODEL), dtype=bf, device=dev) for _ in range(2)]
-        self.gZ = torch.empty((T, D_FF), dtype=bf, device=dev)
+        # G[b] is the gradient entering block b's second layer; the stack's output is G[NB - 1] (loss 0.5 ||Y||^2)
+        self.Xs, self.G = empty(NB, T, D_MODEL), empty(NB, T, D_MODEL)
+        self.Xs[0].copy_(to_dev(si.gaussian((T, D_MODEL), rng)))
+        self.X = [self.Xs[b] for b in range(NB)] + [self.G[NB - 1]]
+        self.Zs, self.As, self.gZs = empty(NB, T, D_FF), empty(NB, T, D_FF), empty(NB, T, D_FF)
+        self.Z, self.A = [self.Zs[b] for b in range(NB)], [self.As[b] for b in range(NB)]
+        self.gZ = self.gZs[0]
+        self.gX = [self.G[b & 1] for b in range(2)]      # (used by callers that run their own per-block backward)
         nbytes = max(lrd.linear_workspace_bytes(T, D_MODEL, D_FF, rank, lrd.BF16, 0),
-                     lrd.linear_workspace_bytes(T, D_FF, D_MODEL, rank, lrd.BF16, 0))
+                     lrd.linear_workspace_bytes(T, D_FF, D_MODEL, rank, lrd.BF16, 0),
+                     lrd.linear_wgrad_batched_workspace_bytes(NB, T, D_MODEL, D_FF, rank, lrd.BF16, 0),
+                     lrd.linear_wgrad_batched_workspace_bytes(NB, T, D_FF, D_MODEL, rank, lrd.BF16, 0))
         self.ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
 
     def forward(self):
@@ -96,14 +107,24 @@ class Stack:
     def backward(self, mask):
         """Loss 0.5 ||Y||^2: the gradient entering the last block is the stack's output."""
         lrd = self.lrd
+        if self.deferred:
+            for b in reversed(range(N_BLOCKS)):
+                l1, l2 = self.layers[b]
+                lrd.linear_bwd_data(self.G[b], l2["V"], l2["U"], self.gZs[b], l2["dH"], self.Z[b], lrd.ACT_GELU, self.ws)
+                lrd.linear_bwd_data(self.gZs[b], l1["V"], l1["U"], self.G[b - 1] if b > 0 else None, l1["dH"], None, lrd.ACT_NONE, self.ws)
+            tu, tv = not mask & 2, not mask & 1
+            for s, dY, X in ((self.st[1], self.G, self.As), (self.st[0], self.gZs, self.Xs)):
+                lrd.linear_wgrad_batched(dY if tu else None, s["H"] if tu else None, s["dH"] if tv else None, X if tv else None,
+                                         s["dV"], s["dU"], mask, self.ws)
+            return
+        # one call per layer; the gradient buffers alternate (the stack's output in G[NB - 1] is read by the first call only)
         g = self.X[N_BLOCKS]
         for b in reversed(range(N_BLOCKS)):
             l1, l2 = self.layers[b]
-            out = self.gX[b & 1]
+            out = self.G[b - 1] if b > 0 else None
             lrd.linear_bwd_act(g, self.A[b], l2["H"], l2["V"], l2["U"], self.gZ, l2["dV"], l2["dU"], None, mask,
                                self.Z[b], lrd.ACT_GELU, self.ws)
-            lrd.linear_bwd(self.gZ, self.X[b], l1["H"], l1["V"], l1["U"], out if b > 0 else None,
-                           l1["dV"], l1["dU"], None, mask, self.ws)
+            lrd.linear_bwd(self.gZ, self.X[b], l1["H"], l1["V"], l1["U"], out, l1["dV"], l1["dU"], None, mask, self.ws)
             g = out
 
     def step(self, mask):
@@ -1226,9 +1247,11 @@ def other_workloads(args, torch, np, si, lrd, graph_ok):
 
     # ---- 12-block FFN stack, 768 -> 3072 -> 768, rank 192, 8192 tokens, sequential freezing
     rank2 = lrd.quantize_rank(int(0.25 * min(D_MODEL, D_FF)), 64)
-    stack = Stack(lrd, torch, np, si, factorize, rank2, seed_stream=0, true_svd=False)
+    stack = Stack(lrd, torch, np, si, factorize, rank2, seed_stream=0, true_svd=False, deferred=True)
     masks = (lrd.freeze_mask(lrd.KIND_SVD, 0), lrd.freeze_mask(lrd.KIND_SVD, 1))
     ms2 = graph_or_eager(torch, lambda parity: stack.step(masks[parity]), k_steps, 2, graph_ok)
+    stack.deferred = False
+    ms2_per_layer = graph_or_eager(torch, lambda parity: stack.step(masks[parity]), k_steps, 2, graph_ok)
     fl2 = (stack.flops(masks[0]) + stack.flops(masks[1])) / 2
     roof2 = 0.0
     for mask in masks:
@@ -1239,8 +1262,9 @@ def other_workloads(args, torch, np, si, lrd, graph_ok):
                 roof2 += roof_us(f + bw, byf + byb)[0] / 2
     del stack
     torch.cuda.empty_cache()
-    res["ffn_stack_rank192"] = dict(workload="config 2: 12 x (768->3072, GELU, 3072->768), rank 192, 8192 tokens, sequential freezing",
-                                    ms_per_step=ms2, tflops=fl2 / (ms2 * 1e-3) / 1e12, tokens_per_s=T_TOKENS / (ms2 * 1e-3),
+    res["ffn_stack_rank192"] = dict(workload="config 2: 12 x (768->3072, GELU, 3072->768), rank 192, 8192 tokens, sequential freezing; "
+                                             "backward in two parts (batched weight gradients), the one-call-per-layer backward beside it",
+                                    ms_per_step=ms2, per_layer_backward_ms_per_step=ms2_per_layer, tflops=fl2 / (ms2 * 1e-3) / 1e12, tokens_per_s=T_TOKENS / (ms2 * 1e-3),
                                     binding_roof_frac=roof2 * 1e-3 / ms2)
 
     # ---- one 4096 x 4096 layer, 16384 tokens: ranks 256 / 257 / 512 / 1024, first factor frozen, and the dense layer

@@ -677,19 +677,12 @@ lrd_status lrd_linear_bwd_data(const void* dY, const void* V, const void* U, voi
     if (!dX) return LRD_OK;
     MatOp d2 = nn(dH_save, r, V, in, dX, in, T, in, r, dt);
     d2.role = LRD_ROLE_DGRAD_DOWN;
-    if (Z_in) {
-        if (dt == LRD_BF16 && in % 8 == 0) {
-            d2.epilogue = EPI_ACT_GRAD;
-            d2.aux = const_cast<void*>(Z_in);
-            d2.ldaux = in;
-            LRD_TRY(run_matop(d2, st));
-        } else {
-            LRD_TRY(run_matop(d2, st));
-            LRD_TRY(gelu_bwd(dX, Z_in, dX, T * in, dt == LRD_BF16, st));
-        }
-    } else {
-        LRD_TRY(run_matop(d2, st));
+    if (Z_in) {      // engines that do not fuse the epilogue run it as a pass of its own (run_matop)
+        d2.epilogue = EPI_ACT_GRAD;
+        d2.aux = const_cast<void*>(Z_in);
+        d2.ldaux = in;
     }
+    LRD_TRY(run_matop(d2, st));
     return LRD_OK;
 }
 
