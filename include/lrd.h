@@ -380,7 +380,7 @@ size_t lrd_svd_factors_workspace_bytes(int64_t out, int64_t in);
  *      each determined up to a common sign of its U column and V row;
  *   sigma_host   host, nullable: all min(out,in) singular values, descending (eq. 3's error is
  *                the sum of the squares past r);
- *   sweeps_host  host, nullable: Jacobi sweeps used.
+ *   sweeps_host  host, nullable: Jacobi sweeps used (those on the Gram matrix of a wide weight included).
  * LRD_ERR_INVALID_ARG (NULL, sizes, r > min(out,in)), LRD_ERR_ALIGNMENT (16 bytes),
  * LRD_ERR_WORKSPACE, LRD_ERR_RUNTIME (launch failure or no convergence in 60 sweeps).
  */

@@ -9,6 +9,14 @@
 // tournament step are independent and run as one launch, one workgroup per pair.  A sweep is
 // p - 1 (p even) or p (p odd) such steps; after each sweep the host reads the number of rotations
 // applied and stops at zero.  These calls therefore synchronise the stream.
+//
+// A matrix at least twice as wide as it is tall is preconditioned first: the same iteration runs on
+// its small Gram matrix G = M.M^T [p x p] (rows of length p instead of q, a fraction of the traffic
+// per sweep), collecting the rotations in Q; then M is replaced by Q.M, whose rows are already
+// orthogonal up to the tolerance of that first phase, and the iteration proper needs only the sweep
+// that finds nothing left to rotate (or one or two more) instead of a dozen.  The convergence test and its
+// tolerance on the rows of M are the same either way, so the result has the accuracy of the plain
+// iteration; the Gram matrix only supplies the starting basis.
 #include <algorithm>
 #include <cmath>
 #include <numeric>
@@ -22,7 +30,13 @@ namespace {
 
 constexpr int FT = 256;                 // threads per workgroup in this file
 constexpr double JACOBI_TOL = 1e-14;    // rows count as orthogonal when |a.b| <= tol * |a| |b|
+// The same test on the rows of the Gram matrix.  Taken as tight as the main one: 13 sweeps there and a single
+// (empty) sweep on M for a 768 x 3072 weight, against 12 + 3 at 1e-11 and 11 + 5 at 1e-7; a sweep on the
+// Gram matrix costs a fraction of one on M.
+constexpr double GRAM_TOL = 1e-14;
 constexpr int MAX_SWEEPS = 60;
+
+inline bool preconditioned(int64_t p, int64_t q) { return p >= 32 && q >= 2 * p; }
 
 inline size_t round256(size_t b) { return (b + 255) & ~size_t(255); }
 
@@ -69,7 +83,8 @@ __global__ __launch_bounds__(FT) void jacobi_step_kernel(double* __restrict__ M,
                                                          int step, double tol, unsigned int* __restrict__ rotations, BatchStride bs)
 {
     M += blockIdx.y * bs.bm; Q += blockIdx.y * bs.bq;
-    __shared__ double scratch[FT];
+    static_assert(FT == 256, "four waves per workgroup");
+    __shared__ double scratch[12];
     __shared__ double cs[2];
     const int k = blockIdx.x, m = n - 1;
     int a, b;
@@ -91,8 +106,24 @@ __global__ __launch_bounds__(FT) void jacobi_step_kernel(double* __restrict__ M,
         sbb += y * y;
         sab += x * y;
     }
-    const double alpha = block_sum(saa, scratch), beta = block_sum(sbb, scratch), gamma = block_sum(sab, scratch);
+    // the three sums in one pass: within each wave by lane shuffles, across the four waves through LDS
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        saa += __shfl_down(saa, off);
+        sbb += __shfl_down(sbb, off);
+        sab += __shfl_down(sab, off);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        const int w = threadIdx.x >> 6;
+        scratch[3 * w] = saa;
+        scratch[3 * w + 1] = sbb;
+        scratch[3 * w + 2] = sab;
+    }
+    __syncthreads();
     if (threadIdx.x == 0) {
+        const double alpha = (scratch[0] + scratch[3]) + (scratch[6] + scratch[9]);
+        const double beta = (scratch[1] + scratch[4]) + (scratch[7] + scratch[10]);
+        const double gamma = (scratch[2] + scratch[5]) + (scratch[8] + scratch[11]);
         double c = 1.0, s = 0.0;
         if (gamma != 0.0 && fabs(gamma) > tol * sqrt(alpha * beta)) {
             const double zeta = (beta - alpha) / (2.0 * gamma);
@@ -223,6 +254,63 @@ __global__ __launch_bounds__(FT) void core_step2_kernel(const double* __restrict
     }
 }
 
+// C[m x n] = A[m x k] . B^T (BT: B is [n x k]) or A . B (B is [k x n]), row-major fp64, 64 x 64 tiles of C per
+// workgroup, 4 x 4 results per thread, 16-deep steps through LDS.  Used twice per preconditioned problem.
+template <bool BT>
+__global__ __launch_bounds__(FT) void product_f64_kernel(const double* __restrict__ A, const double* __restrict__ B, double* __restrict__ C,
+                                                         int m, int n, int k, int64_t a_bs, int64_t b_bs, int64_t c_bs)
+{
+    A += blockIdx.z * a_bs; B += blockIdx.z * b_bs; C += blockIdx.z * c_bs;
+    __shared__ double As[16][65], Bs[16][65];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
+    double acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[a][b] = 0.0;
+    for (int k0 = 0; k0 < k; k0 += 16) {
+        // A tile: 64 rows x 16 k, element e -> row e / 16, k e % 16 (k contiguous in memory)
+#pragma unroll
+        for (int e = tid; e < 64 * 16; e += FT) {
+            const int r = e >> 4, kk = e & 15;
+            As[kk][r] = (i0 + r < m && k0 + kk < k) ? A[(int64_t)(i0 + r) * k + k0 + kk] : 0.0;
+        }
+        if (BT) {
+#pragma unroll
+            for (int e = tid; e < 64 * 16; e += FT) {
+                const int r = e >> 4, kk = e & 15;
+                Bs[kk][r] = (j0 + r < n && k0 + kk < k) ? B[(int64_t)(j0 + r) * k + k0 + kk] : 0.0;
+            }
+        } else {
+#pragma unroll
+            for (int e = tid; e < 64 * 16; e += FT) {
+                const int kk = e >> 6, c = e & 63;
+                Bs[kk][c] = (j0 + c < n && k0 + kk < k) ? B[(int64_t)(k0 + kk) * n + j0 + c] : 0.0;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            double a[4], b[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { a[u] = As[kk][ty + 16 * u]; b[u] = Bs[kk][tx + 16 * u]; }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[u][v] = fma(a[u], b[v], acc[u][v]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int i = i0 + ty + 16 * u, j = j0 + tx + 16 * v;
+            if (i < m && j < n) C[(int64_t)i * n + j] = acc[u][v];
+        }
+}
+
 inline unsigned blocks_for(int64_t items)
 {
     int64_t b = (items + FT - 1) / FT;
@@ -235,12 +323,16 @@ struct JacobiBuffers {
     double* sigma;   // [p]
     int* order;      // [p]
     unsigned int* rotations;
+    double* G = nullptr;    // [p x p] Gram matrix and [p x q] rotated copy of M, preconditioned problems only
+    double* M2 = nullptr;
 };
 
 size_t jacobi_bytes(int64_t p, int64_t q, int64_t batch = 1)
 {
-    return round256((size_t)batch * p * q * 8) + round256((size_t)batch * p * p * 8) + round256((size_t)batch * p * 8) +
-           round256((size_t)batch * p * 4) + 256;
+    size_t b = round256((size_t)batch * p * q * 8) + round256((size_t)batch * p * p * 8) + round256((size_t)batch * p * 8) +
+               round256((size_t)batch * p * 4) + 256;
+    if (preconditioned(p, q)) b += round256((size_t)batch * p * p * 8) + round256((size_t)batch * p * q * 8);
+    return b;
 }
 
 JacobiBuffers carve_jacobi(char*& at, int64_t p, int64_t q, int64_t batch = 1)
@@ -251,6 +343,10 @@ JacobiBuffers carve_jacobi(char*& at, int64_t p, int64_t q, int64_t batch = 1)
     jb.sigma = (double*)at;        at += round256((size_t)batch * p * 8);
     jb.order = (int*)at;           at += round256((size_t)batch * p * 4);
     jb.rotations = (unsigned int*)at; at += 256;
+    if (preconditioned(p, q)) {
+        jb.G = (double*)at;        at += round256((size_t)batch * p * p * 8);
+        jb.M2 = (double*)at;       at += round256((size_t)batch * p * q * 8);
+    }
     return jb;
 }
 
@@ -265,25 +361,55 @@ int64_t jacobi_chunk(int64_t p, int64_t q, int64_t batch)
 // Sweeps until no pair rotates (in any matrix of the batch: one counter, one host read per sweep); then
 // singular values to the host, descending order to the device (both [batch][p]).
 // Returns the sweeps used, or -1 on a runtime error, -2 if MAX_SWEEPS did not suffice.
-int run_jacobi(const JacobiBuffers& jb, int p, int q, std::vector<double>& sigma_host, std::vector<int>& order_host, hipStream_t st,
-               int batch = 1, BatchStride bs = BatchStride{})
+// Sweeps on the rows of Mx [p x len] (rotations collected in Q) until a sweep rotates nothing; returns the
+// sweeps used, -1 on a runtime error, -2 when MAX_SWEEPS did not suffice.
+int sweep_until_orthogonal(double* Mx, double* Q, unsigned int* rotations, int p, int len, double tol, hipStream_t st, int batch,
+                           BatchStride bs)
 {
     const int n = (p + 1) & ~1;       // players of the tournament (one bye when p is odd)
     int sweeps = 0;
     bool converged = p < 2;
     while (!converged && sweeps < MAX_SWEEPS) {
         // the counter is cleared by a kernel-free path the stream orders with the launches
-        if (hipMemsetAsync(jb.rotations, 0, sizeof(unsigned int), st) != hipSuccess) return -1;
+        if (hipMemsetAsync(rotations, 0, sizeof(unsigned int), st) != hipSuccess) return -1;
         for (int step = 0; step < n - 1; ++step)
-            hipLaunchKernelGGL(jacobi_step_kernel, dim3(n / 2, batch), dim3(FT), 0, st, jb.M, jb.Q, p, q, n, step, JACOBI_TOL, jb.rotations, bs);
+            hipLaunchKernelGGL(jacobi_step_kernel, dim3(n / 2, batch), dim3(FT), 0, st, Mx, Q, p, len, n, step, tol, rotations, bs);
         if (hipGetLastError() != hipSuccess) return -1;
         unsigned int count = 0;
-        if (hipMemcpyAsync(&count, jb.rotations, sizeof count, hipMemcpyDeviceToHost, st) != hipSuccess) return -1;
+        if (hipMemcpyAsync(&count, rotations, sizeof count, hipMemcpyDeviceToHost, st) != hipSuccess) return -1;
         if (hipStreamSynchronize(st) != hipSuccess) return -1;
         ++sweeps;
         converged = count == 0;
     }
-    if (!converged) return -2;
+    return converged ? sweeps : -2;
+}
+
+int run_jacobi(JacobiBuffers& jb, int p, int q, std::vector<double>& sigma_host, std::vector<int>& order_host, hipStream_t st,
+               int batch = 1, BatchStride bs = BatchStride{})
+{
+    int sweeps = 0;
+    if (jb.G && jb.M2) {
+        // starting basis from the Gram matrix: G = M.M^T, rows of G made orthogonal (rotations into Q), M <- Q.M
+        const int64_t sm = (int64_t)p * q, sq = (int64_t)p * p;
+        BatchStride gs = bs;
+        gs.bm = sq;                      // the "matrix" of this phase is G: stride p*p, row length p
+        gs.bq = sq;
+        const unsigned tp = (unsigned)((p + 63) / 64), tq = (unsigned)((q + 63) / 64);
+        hipLaunchKernelGGL((product_f64_kernel<true>), dim3(tp, tp, batch), dim3(FT), 0, st, jb.M, jb.M, jb.G, p, p, q, sm, sm, sq);
+        if (hipGetLastError() != hipSuccess) return -1;
+        const int pre = sweep_until_orthogonal(jb.G, jb.Q, jb.rotations, p, p, GRAM_TOL, st, batch, gs);
+        if (pre == -1) return -1;        // (not converged within the limit is no error here: the main phase finishes the job)
+        sweeps += pre > 0 ? pre : MAX_SWEEPS;
+        hipLaunchKernelGGL((product_f64_kernel<false>), dim3(tq, tp, batch), dim3(FT), 0, st, jb.Q, jb.M, jb.M2, p, q, p, sq, sm, sm);
+        if (hipGetLastError() != hipSuccess) return -1;
+        std::swap(jb.M, jb.M2);
+    }
+    BatchStride ms = bs;
+    ms.bm = (int64_t)p * q;
+    ms.bq = (int64_t)p * p;
+    const int main_sweeps = sweep_until_orthogonal(jb.M, jb.Q, jb.rotations, p, q, JACOBI_TOL, st, batch, ms);
+    if (main_sweeps < 0) return main_sweeps;
+    sweeps += main_sweeps;
     hipLaunchKernelGGL(row_norms_kernel, dim3(p, batch), dim3(FT), 0, st, jb.M, q, jb.sigma, bs);
     sigma_host.resize((size_t)p * batch);
     if (hipMemcpyAsync(sigma_host.data(), jb.sigma, (size_t)p * batch * 8, hipMemcpyDeviceToHost, st) != hipSuccess) return -1;
