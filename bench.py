@@ -495,7 +495,8 @@ def cpu_baseline(np, si, oracle, rank, layers=6):
 def rank_sweep(args, torch, lrd):
     """Config 3: one 4096 x 4096 linear, 16384 tokens, bf16; forward + backward time against the rank
     (raw ranks and their quantized neighbours) with nothing / V / U frozen, beside the dense layer.
-    Timing only (parity of these shapes is covered by the tests); prints one JSON line."""
+    Timing only (tests/test_gpu_fullsize.py compares this layer with the oracle at r = 257, 512, 513, 768, 1024 and
+    undecomposed, tests/test_gpu_linear.py at r = 256); prints one JSON line."""
     T, d = 16384, 4096
     bf = torch.bfloat16
     gen = torch.Generator(device="cuda").manual_seed(230903824 + 3)
