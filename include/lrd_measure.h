@@ -78,7 +78,7 @@ lrd_status lrd_measure_mfma_loop(float* sink, int32_t workgroups, int32_t iters,
 
 /*
  * Launches `workgroups` workgroups of four wavefronts that each read `iters` rounds of eight 16-byte
- * words per lane from LDS, in the conflict-free pattern of an operand fragment; the caller times the
+ * words per lane from LDS (ds_read_b128, eight in flight), in the pattern of an operand fragment; the caller times the
  * launch.  *bytes_host (host, nullable) receives the LDS bytes read by the launch (divide by the time
  * and by the compute units the workgroups cover for bytes per second per unit).  sink: device, at least
  * workgroups * 256 words.  Stateless.

@@ -69,8 +69,8 @@ __device__ __forceinline__ float gelu_grad_f(float z)
 // gelu'(z) ~ 1/2 + c R8(c^2) with c = clamp(z, +-4.5) (|error| <= 2.6e-4), least-squares fits on
 // Chebyshev nodes.  No exponential and no reciprocal: 10-12 full-rate instructions per element against
 // ~25 for the form above.  An epilogue that applies the activation to every element of a wide result
-// is bound by exactly this instruction count (the vector unit does not run while the same wave's matrix
-// instructions issue), so it is what the fused epilogues and the bf16 elementwise passes use.
+// spends most of its instructions here (20-25 vector instructions per matrix instruction in the fused
+// kernels), so this is what the fused epilogues and the bf16 elementwise passes use.
 __device__ __forceinline__ float gelu_bf16_f(float z)
 {
     const float c = __builtin_amdgcn_fmed3f(z, -4.0f, 4.0f);

@@ -30,23 +30,30 @@ __global__ __launch_bounds__(256) void mfma_loop_kernel(float* __restrict__ sink
     sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
-// Every lane reads 16 bytes of LDS per access in the pattern of an operand fragment of the matrix
-// instruction (32 rows, a row pitch that spreads them over the banks: no conflicts), 8 accesses per
-// round; nothing else runs, so the launch time is the LDS read time.
+// Every lane reads 16 bytes of LDS per access in the pattern of a k-contiguous operand fragment of the
+// matrix instruction (32 rows at the product kernel's row pitch of 144 bytes, two k halves), eight
+// ds_read_b128 in flight before one wait; nothing else runs, so the launch time is the LDS read time.
+// (Written with the instruction itself: a read through a generic pointer is a flat load, which takes
+// the vector-memory path and measures that instead.)
 __global__ __launch_bounds__(256) void lds_read_kernel(unsigned* __restrict__ sink, int iters)
 {
-    extern __shared__ __align__(16) unsigned char lds_bytes[];
+    typedef __attribute__((address_space(3))) unsigned char lds_byte;
+    __shared__ __align__(16) unsigned char lds_bytes[32768];
     const int tid = threadIdx.x, lane = tid & 63;
     for (int i = tid; i < 8192; i += 256) reinterpret_cast<unsigned*>(lds_bytes)[i] = (unsigned)i;
     __syncthreads();
-    const unsigned char* base = lds_bytes + (lane & 31) * 528 + (lane >> 5) * 16;
+    // largest byte touched: 16384 + 31 * 144 + 16 + 4704 + 15 < 32768
+    const unsigned base = (unsigned)(uintptr_t)(lds_byte*)lds_bytes + (unsigned)((lane & 31) * 144 + (lane >> 5) * 16);
     unsigned acc = 0;
     for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const u32x4 v = *reinterpret_cast<const volatile u32x4*>(base + k * 32);
-            acc += v.x + v.y + v.z + v.w;
-        }
+        const unsigned a = base + ((unsigned)(it & 1) << 14);
+        u32x4 v0, v1, v2, v3, v4, v5, v6, v7;
+        asm volatile("ds_read_b128 %0, %8\n ds_read_b128 %1, %8 offset:32\n ds_read_b128 %2, %8 offset:64\n ds_read_b128 %3, %8 offset:96\n"
+                     "ds_read_b128 %4, %8 offset:4608\n ds_read_b128 %5, %8 offset:4640\n ds_read_b128 %6, %8 offset:4672\n"
+                     "ds_read_b128 %7, %8 offset:4704\n s_waitcnt lgkmcnt(0)"
+                     : "=v"(v0), "=v"(v1), "=v"(v2), "=v"(v3), "=v"(v4), "=v"(v5), "=v"(v6), "=v"(v7)
+                     : "v"(a));
+        acc += v0.x + v1.y + v2.z + v3.w + v4.x + v5.y + v6.z + v7.w;
     }
     sink[(size_t)blockIdx.x * 256 + tid] = acc;
 }
@@ -105,7 +112,7 @@ lrd_status lrd_measure_mfma_loop(float* sink, int32_t workgroups, int32_t iters,
 lrd_status lrd_measure_lds_read(uint32_t* sink, int32_t workgroups, int32_t iters, double* bytes_host, void* hip_stream)
 {
     if (!sink || workgroups < 1 || workgroups > (1 << 20) || iters < 1) return LRD_ERR_INVALID_ARG;
-    hipLaunchKernelGGL(lds_read_kernel, dim3((unsigned)workgroups), dim3(256), 32768, (hipStream_t)hip_stream, sink, (int)iters);
+    hipLaunchKernelGGL(lds_read_kernel, dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)hip_stream, sink, (int)iters);
     if (hipGetLastError() != hipSuccess) return LRD_ERR_RUNTIME;
     if (bytes_host) *bytes_host = (double)workgroups * 256.0 * (double)iters * 8.0 * 16.0;
     return LRD_OK;

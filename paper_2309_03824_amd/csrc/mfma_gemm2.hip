@@ -746,10 +746,9 @@ hipError_t by_tile(const MatOp& op, const Operand& A, const Operand& B, hipStrea
 {
     const int64_t splits = effective_splits(op, nullptr);
     auto wgs = [&](int bm, int bn) { return ceil_div(op.M, bm) * ceil_div(op.N, bn) * splits * (G == GATHER_NONE ? op.batch : 1); };
-    // Large products in every layout: 256 x 256 tiles on eight waves (wave tile 128 x 64: 0.75 KB of LDS
-    // fragment reads per matrix instruction against 1 KB for a 64 x 64 wave tile; LDS reads are what
-    // bounds these kernels).  16384 x 4096 x 4096: forward 551 -> 445 us, data gradient 609 -> 440 us,
-    // weight gradient 538 -> 407 us against 128 x 128 tiles.
+    // Large products in every layout: 256 x 256 tiles on eight waves (wave tile 128 x 64): half the operand
+    // bytes per flop from L2 into LDS of a 128 x 128 tile, and a quarter of the barriers.  16384 x 4096 x 4096:
+    // forward 551 -> 445 us, data gradient 609 -> 440 us, weight gradient 538 -> 407 us against 128 x 128 tiles.
     if constexpr (G == GATHER_NONE && ((sizeof(OutT) == 2 && !A_KM) || (sizeof(OutT) == 4 && A_KM && B_KM))) {
         // (a batch of weight gradients: from 128 tiles on, 213 against 368 us for 36 x [1024 x 256] over 8192 tokens)
         const int64_t enough = (sizeof(OutT) == 4 && op.batch >= 8) ? 128 : 224;
