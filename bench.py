@@ -1083,7 +1083,8 @@ def kernel_roofline(rows):
     if seen and all(k in seen for k in shapes):
         traffic = sum(seen[k] * c for k, c in shapes.items()) / n
     roof.update(traffic=traffic, traffic_note="HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this command, copy-calibrated "
-                "(profiles/encoder_step_hbm_traffic.md); null when this kernel or its shapes were not the profiled ones", kernel=name, avg_us=total_us / n, launches=n, bytes_per_launch=nbytes / n, flops_per_launch=flops / n,
+                "(profiles/encoder_step_hbm_traffic.md, taken at commit d2842f5; csrc/mfma_gemm2.hip's kernel body is unchanged since); "
+                "null when this kernel or its shapes were not the profiled ones", kernel=name, avg_us=total_us / n, launches=n, bytes_per_launch=nbytes / n, flops_per_launch=flops / n,
                 share_of_logged_time=total_us / sum(r["us"] for r in rows), shapes=shapes,
                 note="algorithmic bytes per launch = both operands read once + result written once (+ the activation tensor the "
                      "epilogue writes or reads); duration from HIP events on the launch stream around every launch of this kernel "
